@@ -1,0 +1,68 @@
+"""Pins for the oracle's decoder-layer composition: computational invariance against a
+textbook dense layer written independently (tests/cases.dense_layer_reference)."""
+import numpy as np
+
+from oracle import larosa_oracle as O
+from paper_2507_01299_amd import synth
+from tests import cases
+
+SMALL = synth.LayerShape("small", 64, 64, 32, 176, 16, "f16")
+
+
+def _full_K(layer):
+    layer.K1, layer.K2, layer.K3, layer.K4 = layer.d, layer.d_q, layer.d, layer.d_ff
+
+
+def test_block_layer_full_K_equals_dense_layer():
+    case = cases.build_block_layer(SMALL, 0.4, seed=21, n_cal=512)
+    L = case.layer
+    # unrounded operands: fold in fp64 without the storage rounding
+    L.Wqkv = O.fold_input_side(case.dense["Q_attn"], case.dense["Wqkv"])
+    L.Wgu = O.fold_input_side(case.dense["Q_mlp"], case.dense["Wgu"])
+    L.Wo = case.dense["W"]["o"].astype(np.float64)
+    L.Wdown = case.dense["W"]["down"].astype(np.float64)
+    L.Q_attn, L.Q_mlp = case.dense["Q_attn"], case.dense["Q_mlp"]
+    _full_K(L)
+    X = case.src.draw(4, seed=5)
+    want = cases.dense_layer_reference(case.dense["W"], SMALL, X)
+    for t in range(4):
+        got = O.layer_forward(L, X[t], rounded=False)["x_out"]
+        assert np.max(np.abs(got - want[t])) < 1e-9 * np.max(np.abs(want[t]))
+
+
+def test_folded_stack_with_adapters_full_K_equals_dense_stack():
+    n_layers = 3
+    layers, _, Qs, Ws, src = cases.build_folded_stack(SMALL, n_layers, 0.4, seed=31, n_cal=512, store=False)
+    for A in (l.adapter for l in layers):
+        assert np.max(np.abs(A.T @ A - np.eye(SMALL.d))) < 1e-10        # adapters are orthogonal
+    X = src.draw(3, seed=9)
+    want = X
+    for W in Ws:
+        want = cases.dense_layer_reference(W, SMALL, want)
+    for t in range(3):
+        xt = O.rotate(X[t], Qs[0])                   # Q_0 folded into the embedding
+        for L in layers:
+            _full_K(L)
+            xt = O.layer_forward(L, xt, rounded=False)["x_out"]
+        assert np.max(np.abs(xt - want[t])) < 1e-9 * np.max(np.abs(want[t]))
+
+
+def test_sparse_layer_is_close_to_dense_and_keeps_exact_counts():
+    case = cases.build_block_layer(SMALL, 0.25, seed=41, n_cal=512)
+    L = case.layer
+    xb, x = cases.tokens(case, 2, seed=6)
+    for t in range(2):
+        r = O.layer_forward(L, x[t], rounded=True)
+        for name, K, n in (("idx1", L.K1, L.d), ("idx2", L.K2, L.d_q), ("idx3", L.K3, L.d), ("idx4", L.K4, L.d_ff)):
+            idx = r[name]
+            assert idx.shape == (K,) and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < n
+        # stored tensors are representable in the layer dtype
+        for name in ("h1", "qkv", "o", "x1", "h3", "gu", "h4", "down", "x2", "x_out"):
+            assert np.array_equal(O.round16(r[name], "f16"), r[name])
+        # stage functions replayed on the run's own tensors give the same stages (teacher forcing)
+        assert np.array_equal(O.stage_qkv(L, r["h1"], r["idx1"], "f16"), r["qkv"])
+        assert np.array_equal(O.stage_h4(L, r["gu"], "f16"), r["h4"])
+        assert np.array_equal(O.stage_down(L, r["x1"], r["h4"], r["idx4"], "f16")[1], r["x2"])
+        dense = cases.dense_layer_reference(case.dense["W"], SMALL, x[t])
+        rel = np.linalg.norm(r["x_out"] - dense) / np.linalg.norm(dense)
+        assert rel < 0.2
