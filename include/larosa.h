@@ -1,0 +1,146 @@
+/*
+ * liblarosa -- decode-time hot path of LaRoSA (layerwise rotated sparse activation,
+ * arXiv 2507.01299) for one AMD MI355X (gfx950).
+ *
+ * Per token and per projection the method computes  y = S_k(x Q) (W Q)^T  (Sec. 4.3,
+ * Eq. 9-10): rotate the block input with the layer's orthogonal matrix Q, keep the k
+ * entries of largest magnitude (Eq. 8), and multiply by the folded weight, of which only
+ * the k kept input channels are read (Sec. 4.4).
+ *
+ * Conventions common to every entry point
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates
+ *    nothing, frees nothing, and never synchronises: all work is enqueued on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).
+ *  - 16-bit tensors are IEEE binary16 (LAROSA_F16) or bfloat16 (LAROSA_BF16), row-major,
+ *    with fp32 accumulation inside the kernels and one round-to-nearest-even at each store.
+ *  - A folded weight W' is stored input-channel-major: row-major [d_in][d_out], so that
+ *    input channel i owns one contiguous run of d_out values (Sec. 4.4, point 1: the
+ *    "column-major" layout of the [d_out][d_in] linear-layer weight).
+ *  - Data pointers must be 16-byte aligned; d_out and d must be multiples of 8.
+ *  - Scratch memory comes from the caller's workspace `ws` (256-byte aligned) of at least
+ *    the number of bytes the matching *_workspace_bytes() query returns.  A workspace must
+ *    be passed once through larosa_workspace_init() after allocation (it zeroes the
+ *    arrival counters; the kernels leave them zero again on exit).  Two calls that use the
+ *    same workspace must be ordered on one stream.
+ *  - Return value: LAROSA_OK (0) or a negative larosa_status.  Invalid arguments are
+ *    rejected before anything is enqueued.  LAROSA_EHIP reports a failed launch
+ *    (hipGetLastError() != hipSuccess after enqueueing).
+ */
+#ifndef LAROSA_H
+#define LAROSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LAROSA_F16 = 0, LAROSA_BF16 = 1 } larosa_dtype;
+
+typedef enum {
+  LAROSA_OK = 0,
+  LAROSA_EINVAL = -1,       /* null pointer, size out of range, misalignment, unknown dtype */
+  LAROSA_EUNSUPPORTED = -2, /* valid request outside what the kernels cover (e.g. d > 32768 in Top-K) */
+  LAROSA_EWORKSPACE = -3,   /* workspace missing, misaligned or too small */
+  LAROSA_EHIP = -4          /* the HIP runtime reported an error at launch */
+} larosa_status;
+
+/* Static, NUL-terminated description of a status code.  Never NULL. */
+const char* larosa_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int larosa_version(void);
+
+/* Bytes of workspace that larosa_rotate / larosa_topk / larosa_sparse_gemv need for B tokens
+ * with input width <= d_in_max, output width <= d_out_max and kept count <= K_max.
+ * Pure host function (no device access).  Returns 0 for non-positive arguments. */
+size_t larosa_workspace_bytes(int B, int d_in_max, int d_out_max, int K_max);
+
+/* Zero the arrival counters at the head of a freshly allocated workspace (device pointer,
+ * >= larosa_workspace_bytes(1,8,8,1) bytes).  Enqueued on `stream` as a fill kernel. */
+int larosa_workspace_init(void* ws, size_t ws_bytes, void* stream);
+
+/* Rotation (Sec. 4.3: the rotated activation x Q; App. A: h_i = sum_j x_j Q_ji).
+ *   h[b,i] = sum_j x[b,j] * Q[j,i]
+ * x [B,d], Q [d,d] row-major (row j = input channel j; column i = i-th principal direction),
+ * h [B,d].  Also serves the residual adapter x (Q_l^T Q_{l+1}) (Sec. 4.2) and, being a dense
+ * mat-vec over an input-channel-major matrix, the dense comparator.
+ * `Q` may be rectangular for that last use: pass d_out != d through larosa_dense_gemv. */
+int larosa_rotate(const void* x, const void* Q, void* h, int B, int d, larosa_dtype t,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Dense product over an input-channel-major matrix:  y[b,o] = sum_j x[b,j] * Wp[j,o].
+ * x [B,d_in], Wp [d_in,d_out], y [B,d_out].  (Eq. 1 with the stored layout; the K = d_in
+ * special case of the sparse projection, used as the dense baseline on the same GPU.) */
+int larosa_dense_gemv(const void* Wp, const void* x, void* y, int B, int d_in, int d_out,
+                      larosa_dtype t, void* ws, size_t ws_bytes, void* stream);
+
+/* Top-K sparsifier S_k (Sec. 4.3, Eq. 8): for each token b, the K indices of largest |h[b,:]|.
+ * Magnitudes are compared on the stored 16-bit values (sign bit cleared, bit pattern as an
+ * unsigned integer); ties go to the larger magnitude, then to the lower index; exactly K
+ * indices are produced, in ascending order.
+ * h [B,d]; idx [B,K] int32 (output); vals [B,K] (output, nullable) receives h[b, idx[b,t]].
+ * 1 <= K <= d <= 32768. */
+int larosa_topk(const void* h, int B, int d, int K, int32_t* idx, void* vals,
+                larosa_dtype t, void* ws, size_t ws_bytes, void* stream);
+
+/* Column-sparse projection (Sec. 4.3, Eq. 10; Sec. 4.4 point 3):
+ *   y[b,o] = sum_{t<K} h[b, idx[b,t]] * Wp[idx[b,t], o]
+ * Only the rows of Wp named by idx are read.  Wp [d_in,d_out] input-channel-major,
+ * h [B,d_in], idx [B,K] int32 with 0 <= idx < d_in (per-token index sets; need not be sorted,
+ * must not repeat within a token), y [B,d_out] (output). */
+int larosa_sparse_gemv(const void* Wp, const void* h, const int32_t* idx, void* y,
+                       int B, int d_in, int d_out, int K, larosa_dtype t,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* One decoder layer (Fig. 2; Sec. 3.1 for h1..h4; Sec. 4.2-4.3).  All pointers device, borrowed
+ * for the duration of the call. */
+typedef struct {
+  int d, d_q, d_kv, d_ff;     /* hidden, q/o width, k/v width, intermediate */
+  int head_dim;               /* d_q and d_kv are multiples of it; (d_q/head_dim) % (d_kv/head_dim) == 0 */
+  int K1, K2, K3, K4;         /* kept counts for h1 (d), h2 (d_q), h3 (d), h4 (d_ff) */
+  const void* Wqkv;           /* [d, d_q+2*d_kv]  q|k|v, folded with Q^T on the input side when h1 is rotated */
+  const void* Wo;             /* [d_q, d]         meets the unrotated h2 (Q = I, Sec. 4.3) */
+  const void* Wgu;            /* [d, 2*d_ff]      gate|up, folded like Wqkv */
+  const void* Wdown;          /* [d_ff, d]        meets the unrotated h4 */
+  const void* Q_attn;         /* [d,d] or NULL: NULL = x already arrives in the layer's basis (folded form) */
+  const void* Q_mlp;          /* [d,d] or NULL */
+  const void* adapter;        /* [d,d] Q_l^T Q_{l+1} applied to the layer output, or NULL */
+  const void* rms_attn;       /* [d] pre-norm scale or NULL = 1 */
+  const void* rms_mlp;        /* [d] or NULL */
+  float rms_eps;              /* < 0 disables both pre-norms */
+  int attn_mode;              /* 0: context-length-1 attention (softmax over one key = 1, so each query
+                                    head outputs the value head of its group).  No other mode yet. */
+  larosa_dtype dtype;
+} larosa_layer;
+
+/* Optional copies of every stage (device pointers, each nullable), for stage-by-stage checks:
+ * h1 [B,d]; idx1 [B,K1]; qkv [B,d_q+2d_kv]; h2 [B,d_q]; idx2 [B,K2]; o [B,d]; x1 [B,d];
+ * h3 [B,d]; idx3 [B,K3]; gu [B,2d_ff]; h4 [B,d_ff]; idx4 [B,K4]; down [B,d]; x2 [B,d]. */
+typedef struct {
+  void *h1, *qkv, *h2, *o, *x1, *h3, *gu, *h4, *down, *x2;
+  int32_t *idx1, *idx2, *idx3, *idx4;
+} larosa_trace;
+
+/* Workspace bytes larosa_layer_forward needs for this layer and B tokens (host only). */
+size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B);
+
+/* x [B,d] -> x_out [B,d]:
+ *   h1 = R(norm(x) Q_attn); qkv = R(S_K1(h1) Wqkv); h2 = attention core of qkv;
+ *   o = R(S_K2(h2) Wo); x1 = R(x + o); h3 = R(norm(x1) Q_mlp); gu = R(S_K3(h3) Wgu);
+ *   h4 = R(SiLU(gate) * up); down = R(S_K4(h4) Wdown); x2 = R(x1 + down);
+ *   x_out = R(x2 adapter) or x2.         R = one rounding to the layer dtype.
+ * trace may be NULL.  x_out must not alias x. */
+int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int B,
+                         const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
+
+/* Kernel launch tuning for experiments (host state, not thread-safe): key 0 = target number
+ * of workgroups of the row-streaming kernels, key 1 = minimum rows per workgroup,
+ * key 2 = kernel variant.  Returns LAROSA_EINVAL for an unknown key or a value out of range. */
+int larosa_set_tuning(int key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAROSA_H */

@@ -1,0 +1,310 @@
+// C ABI of liblarosa: argument checks, workspace carving, launch sequencing.
+// No arithmetic of the method lives here; every step runs in the kernels.
+#include "../../include/larosa.h"
+
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+using namespace larosa;
+
+namespace {
+
+constexpr size_t kCounterSlots = 16384;                       // u32 arrival counters at the head of a workspace
+constexpr size_t kCounterBytes = kCounterSlots * sizeof(unsigned);
+constexpr int kMaxTopkD = 32768;
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool dtype_ok(int t) { return t == LAROSA_F16 || t == LAROSA_BF16; }
+
+size_t gemv_partial_bytes_bound(int B, int d_out_max) {
+  const int sc = gemv_strip_cols();
+  const long nstrips = (d_out_max + sc - 1) / sc;
+  long G = tuning().g_target;
+  if (G < nstrips) G = nstrips;
+  return static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * sc * sizeof(float);
+}
+
+struct Carver {
+  char* base;
+  size_t off, cap;
+  bool ok = true;
+  void* take(size_t bytes) {
+    off = round_up(off, 256);
+    if (off + bytes > cap) { ok = false; return nullptr; }
+    void* p = base + off;
+    off += bytes;
+    return p;
+  }
+};
+
+// One launch of the row-streaming kernel with its plan and workspace checks.
+int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
+  const GemvPlan p = plan_gemv(a.d_out, a.K);
+  if (static_cast<size_t>(a.B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  const size_t need = kCounterBytes + static_cast<size_t>(a.B) * p.partial_floats * sizeof(float);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  a.chunk = p.chunk;
+  a.G = p.G;
+  a.nstrips = p.nstrips;
+  a.counters = static_cast<unsigned*>(ws);
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  return launch_gemv(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
+int check_gemv_shapes(int B, int d_in, int d_out, int K) {
+  if (B < 1 || d_in < 8 || d_out < 8 || K < 1 || K > d_in) return LAROSA_EINVAL;
+  if (d_in % 8 || d_out % 8) return LAROSA_EINVAL;
+  if (static_cast<long>((d_out + 511) / 512) * K >= (1L << 30)) return LAROSA_EUNSUPPORTED;
+  if (B > 65535) return LAROSA_EUNSUPPORTED;
+  return LAROSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* larosa_status_string(int status) {
+  switch (status) {
+    case LAROSA_OK: return "ok";
+    case LAROSA_EINVAL: return "invalid argument";
+    case LAROSA_EUNSUPPORTED: return "unsupported size";
+    case LAROSA_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LAROSA_EHIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int larosa_version(void) { return 100; }
+
+size_t larosa_workspace_bytes(int B, int d_in_max, int d_out_max, int K_max) {
+  if (B < 1 || d_in_max < 1 || d_out_max < 1 || K_max < 1) return 0;
+  return round_up(kCounterBytes + gemv_partial_bytes_bound(B, d_out_max), 256);
+}
+
+int larosa_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws || !aligned(ws, 256) || ws_bytes < kCounterBytes) return LAROSA_EWORKSPACE;
+  return launch_fill_u32(static_cast<unsigned*>(ws), kCounterSlots, 0u, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess
+             ? LAROSA_OK
+             : LAROSA_EHIP;
+}
+
+int larosa_dense_gemv(const void* Wp, const void* x, void* y, int B, int d_in, int d_out, larosa_dtype t,
+                      void* ws, size_t ws_bytes, void* stream) {
+  if (!Wp || !x || !y || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(Wp, 16) || !aligned(x, 16) || !aligned(y, 16)) return LAROSA_EINVAL;
+  if (int rc = check_gemv_shapes(B, d_in, d_out, d_in)) return rc;
+  GemvArgs a{};
+  a.W = static_cast<const uint16_t*>(Wp);
+  a.h = static_cast<const uint16_t*>(x);
+  a.idx = nullptr;
+  a.y = static_cast<uint16_t*>(y);
+  a.d_in = d_in; a.d_out = d_out; a.K = d_in; a.B = B;
+  return run_gemv(a, t == LAROSA_BF16, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int larosa_rotate(const void* x, const void* Q, void* h, int B, int d, larosa_dtype t, void* ws,
+                  size_t ws_bytes, void* stream) {
+  return larosa_dense_gemv(Q, x, h, B, d, d, t, ws, ws_bytes, stream);
+}
+
+int larosa_topk(const void* h, int B, int d, int K, int32_t* idx, void* vals, larosa_dtype t, void* ws,
+                size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  if (!h || !idx || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(h, 16) || !aligned(idx, 4) || (vals && !aligned(vals, 2))) return LAROSA_EINVAL;
+  if (B < 1 || d < 8 || d % 8 || K < 1 || K > d) return LAROSA_EINVAL;
+  if (d > kMaxTopkD || B > 65535) return LAROSA_EUNSUPPORTED;
+  return launch_topk(static_cast<const uint16_t*>(h), B, d, K, idx, static_cast<uint16_t*>(vals),
+                     static_cast<hipStream_t>(stream)) == hipSuccess
+             ? LAROSA_OK
+             : LAROSA_EHIP;
+}
+
+int larosa_sparse_gemv(const void* Wp, const void* h, const int32_t* idx, void* y, int B, int d_in, int d_out,
+                       int K, larosa_dtype t, void* ws, size_t ws_bytes, void* stream) {
+  if (!Wp || !h || !idx || !y || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(Wp, 16) || !aligned(h, 16) || !aligned(y, 16) || !aligned(idx, 4)) return LAROSA_EINVAL;
+  if (int rc = check_gemv_shapes(B, d_in, d_out, K)) return rc;
+  GemvArgs a{};
+  a.W = static_cast<const uint16_t*>(Wp);
+  a.h = static_cast<const uint16_t*>(h);
+  a.idx = idx;
+  a.y = static_cast<uint16_t*>(y);
+  a.d_in = d_in; a.d_out = d_out; a.K = K; a.B = B;
+  return run_gemv(a, t == LAROSA_BF16, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------------
+// decoder layer
+// ---------------------------------------------------------------------------------------------
+
+static int check_layer(const larosa_layer* L, int B) {
+  if (!L || B < 1 || B > 65535) return LAROSA_EINVAL;
+  if (!dtype_ok(L->dtype)) return LAROSA_EINVAL;
+  if (L->d < 8 || L->d_q < 8 || L->d_kv < 8 || L->d_ff < 8) return LAROSA_EINVAL;
+  if (L->d % 8 || L->d_q % 8 || L->d_kv % 8 || L->d_ff % 8) return LAROSA_EINVAL;
+  if (L->head_dim < 8 || L->head_dim % 8 || L->d_q % L->head_dim || L->d_kv % L->head_dim) return LAROSA_EINVAL;
+  if ((L->d_q / L->head_dim) % (L->d_kv / L->head_dim)) return LAROSA_EINVAL;
+  if (L->K1 < 1 || L->K1 > L->d || L->K2 < 1 || L->K2 > L->d_q || L->K3 < 1 || L->K3 > L->d || L->K4 < 1 ||
+      L->K4 > L->d_ff)
+    return LAROSA_EINVAL;
+  if (!L->Wqkv || !L->Wo || !L->Wgu || !L->Wdown) return LAROSA_EINVAL;
+  const void* ptrs[] = {L->Wqkv, L->Wo, L->Wgu, L->Wdown, L->Q_attn, L->Q_mlp, L->adapter, L->rms_attn, L->rms_mlp};
+  for (const void* p : ptrs)
+    if (p && !aligned(p, 16)) return LAROSA_EINVAL;
+  if (L->attn_mode != 0) return LAROSA_EUNSUPPORTED;
+  if (L->d > kMaxTopkD || L->d_q > kMaxTopkD || L->d_ff > kMaxTopkD) return LAROSA_EUNSUPPORTED;
+  return LAROSA_OK;
+}
+
+static int max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+
+static size_t layer_gemv_ws(const larosa_layer* L, int B) {
+  return larosa_workspace_bytes(B, max3(L->d, L->d_q, L->d_ff), max3(L->d_q + 2 * L->d_kv, 2 * L->d_ff, L->d),
+                                max3(L->d, L->d_q, L->d_ff));
+}
+
+size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
+  if (check_layer(L, B) != LAROSA_OK) return 0;
+  const size_t E = 2, Bz = static_cast<size_t>(B);
+  size_t s = layer_gemv_ws(L, B);
+  const size_t widths[] = {(size_t)L->d, (size_t)(L->d_q + 2 * L->d_kv), (size_t)L->d_q, (size_t)L->d,
+                           (size_t)L->d, (size_t)L->d, (size_t)(2 * L->d_ff), (size_t)L->d_ff,
+                           (size_t)L->d, (size_t)L->d};
+  for (size_t w : widths) s += round_up(Bz * w * E, 256) + 256;
+  const int Ks[] = {L->K1, L->K2, L->K3, L->K4};
+  for (int k : Ks) s += round_up(Bz * k * sizeof(int32_t), 256) + 256;
+  return s;
+}
+
+int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, int B, const larosa_trace* tr,
+                         void* ws, size_t ws_bytes, void* stream) {
+  if (int rc = check_layer(L, B)) return rc;
+  if (!x_in || !x_out || x_in == x_out || !aligned(x_in, 16) || !aligned(x_out, 16)) return LAROSA_EINVAL;
+  if (!ws || !aligned(ws, 256) || ws_bytes < larosa_layer_workspace_bytes(L, B)) return LAROSA_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = L->dtype == LAROSA_BF16;
+  const size_t Bz = static_cast<size_t>(B);
+  const int d = L->d, d_q = L->d_q, d_kv = L->d_kv, d_ff = L->d_ff;
+  const int d_qkv = d_q + 2 * d_kv;
+  const bool norm = L->rms_eps >= 0.f;
+
+  const size_t gws = layer_gemv_ws(L, B);
+  Carver cv{static_cast<char*>(ws), gws, ws_bytes};
+  auto buf16 = [&](void* traced, size_t width) {
+    return static_cast<uint16_t*>(traced ? traced : cv.take(Bz * width * 2));
+  };
+  auto bufidx = [&](int32_t* traced, int K) {
+    return traced ? traced : static_cast<int32_t*>(cv.take(Bz * K * sizeof(int32_t)));
+  };
+  static const larosa_trace kNoTrace{};
+  const larosa_trace& T = tr ? *tr : kNoTrace;
+  uint16_t* h1 = buf16(T.h1, d);
+  uint16_t* qkv = buf16(T.qkv, d_qkv);
+  uint16_t* h2 = buf16(T.h2, d_q);
+  uint16_t* o = buf16(T.o, d);
+  uint16_t* x1 = buf16(T.x1, d);
+  uint16_t* h3 = buf16(T.h3, d);
+  uint16_t* gu = buf16(T.gu, 2 * d_ff);
+  uint16_t* h4 = buf16(T.h4, d_ff);
+  uint16_t* down = buf16(T.down, d);
+  uint16_t* x2 = L->adapter ? buf16(T.x2, d) : static_cast<uint16_t*>(x_out);
+  int32_t* idx1 = bufidx(T.idx1, L->K1);
+  int32_t* idx2 = bufidx(T.idx2, L->K2);
+  int32_t* idx3 = bufidx(T.idx3, L->K3);
+  int32_t* idx4 = bufidx(T.idx4, L->K4);
+  if (!cv.ok) return LAROSA_EWORKSPACE;
+  const uint16_t* x = static_cast<const uint16_t*>(x_in);
+
+#define LAROSA_TRY(expr)                 \
+  do {                                   \
+    const int rc__ = (expr);             \
+    if (rc__ != LAROSA_OK) return rc__;  \
+  } while (0)
+#define LAROSA_HIP(expr)                               \
+  do {                                                 \
+    if ((expr) != hipSuccess) return LAROSA_EHIP;      \
+  } while (0)
+
+  // block input: pre-norm, rotation, one rounding
+  auto block_input = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* dst) -> int {
+    if (Q) {
+      GemvArgs a{};
+      a.W = static_cast<const uint16_t*>(Q);
+      a.h = src; a.y = dst;
+      a.d_in = d; a.d_out = d; a.K = d; a.B = B;
+      if (norm) {
+        a.rms_src = src;
+        a.rms_eps = L->rms_eps;
+        a.coef_scale = static_cast<const uint16_t*>(scale);
+      }
+      return run_gemv(a, bf, ws, gws, st);
+    }
+    if (norm)
+      return launch_rmsnorm(src, static_cast<const uint16_t*>(scale), dst, B, d, L->rms_eps, bf, st) == hipSuccess
+                 ? LAROSA_OK
+                 : LAROSA_EHIP;
+    return launch_copy_u16(src, dst, Bz * d, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+  };
+  auto sparse = [&](const void* W, const uint16_t* h, const int32_t* idx, uint16_t* y, int d_in, int d_out, int K,
+                    const uint16_t* residual, uint16_t* y_pre) -> int {
+    GemvArgs a{};
+    a.W = static_cast<const uint16_t*>(W);
+    a.h = h; a.idx = idx; a.y = y;
+    a.d_in = d_in; a.d_out = d_out; a.K = K; a.B = B;
+    a.residual = residual; a.y_pre = y_pre;
+    return run_gemv(a, bf, ws, gws, st);
+  };
+
+  // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
+  LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
+  LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, st));
+  LAROSA_TRY(sparse(L->Wqkv, h1, idx1, qkv, d, d_qkv, L->K1, nullptr, nullptr));
+  LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
+  LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, st));
+  LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, x, o));
+  // MLP block: h3 -> gate|up -> h4 -> down -> + residual
+  LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
+  LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, st));
+  LAROSA_TRY(sparse(L->Wgu, h3, idx3, gu, d, 2 * d_ff, L->K3, nullptr, nullptr));
+  LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
+  LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, st));
+  LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+  // residual adapter
+  if (L->adapter) {
+    GemvArgs a{};
+    a.W = static_cast<const uint16_t*>(L->adapter);
+    a.h = x2; a.y = static_cast<uint16_t*>(x_out);
+    a.d_in = d; a.d_out = d; a.K = d; a.B = B;
+    LAROSA_TRY(run_gemv(a, bf, ws, gws, st));
+  } else if (T.x2) {
+    LAROSA_HIP(launch_copy_u16(x2, static_cast<uint16_t*>(T.x2), Bz * d, st));
+  }
+#undef LAROSA_TRY
+#undef LAROSA_HIP
+  return LAROSA_OK;
+}
+
+int larosa_set_tuning(int key, int value) {
+  switch (key) {
+    case 0:
+      if (value < 1 || value > 4096) return LAROSA_EINVAL;
+      tuning().g_target = value;
+      return LAROSA_OK;
+    case 1:
+      if (value < 1 || value > 1 << 20) return LAROSA_EINVAL;
+      tuning().min_rows = value;
+      return LAROSA_OK;
+    case 2:
+      if (value < 0 || value > 5) return LAROSA_EINVAL;
+      tuning().variant = value;
+      return LAROSA_OK;
+    default:
+      return LAROSA_EINVAL;
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// 16-bit storage formats and small wave/block helpers shared by the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace larosa {
+
+constexpr int kWave = 64;
+
+struct F16 {
+  static __device__ __forceinline__ float to_f32(uint16_t b) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, b));
+  }
+  static __device__ __forceinline__ uint16_t from_f32(float f) {      // round to nearest even
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+  }
+  // two packed values in one dword -> two floats
+  static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+    lo = to_f32(static_cast<uint16_t>(w & 0xFFFFu));
+    hi = to_f32(static_cast<uint16_t>(w >> 16));
+  }
+};
+
+struct BF16 {
+  static __device__ __forceinline__ float to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+  }
+  static __device__ __forceinline__ uint16_t from_f32(float f) {      // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+  }
+  static __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xFFFF0000u);
+  }
+};
+
+template <typename T>
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+  T::unpack2(v.x, f[0], f[1]);
+  T::unpack2(v.y, f[2], f[3]);
+  T::unpack2(v.z, f[4], f[5]);
+  T::unpack2(v.w, f[6], f[7]);
+}
+
+template <typename T>
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  uint4 v;
+  v.x = static_cast<uint32_t>(T::from_f32(f[0])) | (static_cast<uint32_t>(T::from_f32(f[1])) << 16);
+  v.y = static_cast<uint32_t>(T::from_f32(f[2])) | (static_cast<uint32_t>(T::from_f32(f[3])) << 16);
+  v.z = static_cast<uint32_t>(T::from_f32(f[4])) | (static_cast<uint32_t>(T::from_f32(f[5])) << 16);
+  v.w = static_cast<uint32_t>(T::from_f32(f[6])) | (static_cast<uint32_t>(T::from_f32(f[7])) << 16);
+  return v;
+}
+
+// value after one storage rounding
+template <typename T>
+__device__ __forceinline__ float round_store(float f) { return T::to_f32(T::from_f32(f)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// inclusive prefix sum across the 64 lanes of a wave
+__device__ __forceinline__ unsigned wave_scan_inclusive(unsigned v, int lane) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    unsigned n = __shfl_up(v, o, kWave);
+    if (lane >= o) v += n;
+  }
+  return v;
+}
+
+}  // namespace larosa

@@ -1,0 +1,168 @@
+"""GPU parity of the single kernels, through the C ABI, against the CPU oracle on the same
+seeded inputs: rotation and sparse projection within 2e-3 relative L2, Top-K indices equal."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import larosa_oracle as O
+from paper_2507_01299_amd import synth
+from tests.gpu_util import REL_L2_TOL, rel_l2, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api(gpu_device):
+    from paper_2507_01299_amd import api as A
+    A.lib()
+    return A
+
+
+@pytest.fixture(scope="module")
+def ws(api):
+    return api.workspace(8, 32768, 32768, 32768)
+
+
+def _heavy_vector(rng, B, d, dtype):
+    v = rng.standard_normal((B, d)) * (np.arange(1, d + 1) ** -0.6)[None, :]
+    v[:, rng.choice(d, 4, replace=False)] *= 20
+    bits = O.encode16(v, dtype)
+    return bits, O.decode16(bits, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d", [(1, 512), (3, 1096), (1, 8), (2, 2048)])
+def test_rotate_matches_oracle(api, ws, dtype, B, d):
+    print(f"rotate dtype={dtype} B={B} d={d}", flush=True)
+    rng = np.random.default_rng(100 + d + B)
+    Q = synth.planted_basis(d, seed=d)
+    qb = O.encode16(Q, dtype)
+    xb, x = _heavy_vector(rng, B, d, dtype)
+    h = torch.zeros(B, d, dtype=api.torch_dtype(dtype), device="cuda:0")
+    api.rotate(to_dev(xb, dtype), to_dev(qb, dtype), h, dtype, ws)
+    torch.cuda.synchronize()
+    want = O.round16(O.rotate(x, O.decode16(qb, dtype)), dtype)      # the output is a stored 16-bit tensor
+    got = O.decode16(to_bits(h), dtype)
+    for b in range(B):
+        assert rel_l2(got[b], want[b]) <= REL_L2_TOL
+    # identity rotation returns the input bits
+    eye = O.encode16(np.eye(d), dtype)
+    api.rotate(to_dev(xb, dtype), to_dev(eye, dtype), h, dtype, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(h), xb)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d,K", [(1, 512, 256), (1, 4096, 2457), (2, 4096, 1), (1, 4096, 4096), (3, 11008, 6604),
+                                   (1, 14336, 8601), (2, 28672, 17203), (1, 32768, 5), (1, 8, 3), (4, 1000, 999),
+                                   (1, 8192, 4915)])
+def test_topk_indices_are_exact(api, dtype, B, d, K):
+    print(f"topk dtype={dtype} B={B} d={d} K={K}", flush=True)
+    rng = np.random.default_rng(7 * d + K)
+    hb, _ = _heavy_vector(rng, B, d, dtype)
+    idx = torch.full((B, K), -1, dtype=torch.int32, device="cuda:0")
+    vals = torch.zeros(B, K, dtype=api.torch_dtype(dtype), device="cuda:0")
+    api.topk(to_dev(hb, dtype), K, idx, dtype, vals=vals)
+    torch.cuda.synchronize()
+    got = idx.cpu().numpy()
+    gv = to_bits(vals)
+    for b in range(B):
+        want = O.topk_indices(hb[b], K)
+        assert np.array_equal(got[b], want)
+        assert np.array_equal(gv[b], hb[b][want])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_topk_ties_and_special_values(api, dtype):
+    d = 4096
+    rng = np.random.default_rng(3)
+    cases = []
+    cases.append(np.full(d, 0x3C00, np.uint16))                                     # all equal
+    few = rng.choice(np.array([0x3C00, 0xBC00, 0x3800, 0x0000, 0x8000], np.uint16), d)   # five values, many ties
+    cases.append(few)
+    sp = O.encode16(rng.standard_normal(d), dtype)
+    inf, ninf, nan = (0x7C00, 0xFC00, 0x7E01) if dtype == "f16" else (0x7F80, 0xFF80, 0x7FC1)
+    sp[[5, 900, 4095]] = [inf, nan, ninf]
+    sp[[17, 18]] = [0x0000, 0x8000]
+    cases.append(sp)
+    cases.append(np.repeat(O.encode16(rng.standard_normal(d // 4), dtype), 4))        # GQA-style repeats
+    hb = np.stack(cases)
+    for K in (1, 2, 1000, 2457, 4095, 4096):
+        idx = torch.full((hb.shape[0], K), -1, dtype=torch.int32, device="cuda:0")
+        api.topk(to_dev(hb, dtype), K, idx, dtype)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy()
+        for b in range(hb.shape[0]):
+            assert np.array_equal(got[b], O.topk_indices(hb[b], K)), (b, K)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d_in,d_out,K", [(1, 512, 1024, 256), (1, 512, 1000, 512), (3, 768, 1544, 300),
+                                            (1, 64, 8, 1), (2, 2048, 6152, 1229), (1, 4096, 512, 4096)])
+def test_sparse_gemv_matches_oracle(api, ws, dtype, B, d_in, d_out, K):
+    print(f"sparse_gemv dtype={dtype} B={B} d_in={d_in} d_out={d_out} K={K}", flush=True)
+    rng = np.random.default_rng(d_in + d_out + K)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, seed=d_out + K), dtype)
+    hb, h = _heavy_vector(rng, B, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    y = torch.zeros(B, d_out, dtype=api.torch_dtype(dtype), device="cuda:0")
+    dW = to_dev(wb, dtype)
+    api.sparse_gemv(dW, to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+    torch.cuda.synchronize()
+    W = O.decode16(wb, dtype)
+    got = O.decode16(to_bits(y), dtype)
+    for b in range(B):
+        want = O.round16(O.sparse_project_gather(h[b], idx[b], W), dtype)   # stored 16-bit output
+        assert rel_l2(got[b], want) <= REL_L2_TOL
+        assert rel_l2(got[b], O.round16(O.sparse_project_masked(h[b], idx[b], W), dtype)) <= REL_L2_TOL
+    # unsorted index order is allowed and changes nothing but rounding order
+    perm = np.stack([rng.permutation(idx[b]) for b in range(B)]).astype(np.int32)
+    y2 = torch.zeros_like(y)
+    api.sparse_gemv(dW, to_dev(hb, dtype), torch.from_numpy(perm).cuda(), y2, dtype, ws)
+    torch.cuda.synchronize()
+    got2 = O.decode16(to_bits(y2), dtype)
+    for b in range(B):
+        assert rel_l2(got2[b], O.round16(O.sparse_project_gather(h[b], idx[b], W), dtype)) <= REL_L2_TOL
+
+
+def test_sparse_gemv_full_K_equals_dense_gemv_and_is_deterministic(api, ws):
+    dtype, d_in, d_out = "f16", 1024, 2568
+    rng = np.random.default_rng(5)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, seed=1), dtype)
+    hb, h = _heavy_vector(rng, 2, d_in, dtype)
+    ident = np.tile(np.arange(d_in, dtype=np.int32), (2, 1))
+    dW, dh = to_dev(wb, dtype), to_dev(hb, dtype)
+    y1 = torch.zeros(2, d_out, dtype=torch.float16, device="cuda:0")
+    y2 = torch.zeros_like(y1)
+    y3 = torch.zeros_like(y1)
+    api.sparse_gemv(dW, dh, torch.from_numpy(ident).cuda(), y1, dtype, ws)
+    api.dense_gemv(dW, dh, y2, dtype, ws)
+    api.sparse_gemv(dW, dh, torch.from_numpy(ident).cuda(), y3, dtype, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(y1), to_bits(y2))
+    assert np.array_equal(to_bits(y1), to_bits(y3))
+    want = O.round16(h @ O.decode16(wb, dtype), dtype)
+    assert rel_l2(O.decode16(to_bits(y1), dtype), want) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("variant,g_target,min_rows", [(0, 64, 4), (1, 2048, 1), (2, 256, 16), (3, 1024, 8),
+                                                        (4, 512, 2), (5, 4096, 64)])
+def test_sparse_gemv_every_launch_shape(api, variant, g_target, min_rows):
+    """Each kernel shape variant and work split gives the same answer (within rounding order)."""
+    dtype, d_in, d_out, K = "bf16", 1536, 3080, 777
+    rng = np.random.default_rng(11)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, seed=2), dtype)
+    hb, h = _heavy_vector(rng, 2, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    try:
+        api.set_tuning(2, variant); api.set_tuning(0, g_target); api.set_tuning(1, min_rows)
+        ws = api.workspace(2, d_in, d_out, K)
+        y = torch.zeros(2, d_out, dtype=torch.bfloat16, device="cuda:0")
+        api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+        torch.cuda.synchronize()
+    finally:
+        api.set_tuning(2, 0); api.set_tuning(0, 1024); api.set_tuning(1, 8)
+    W = O.decode16(wb, dtype)
+    got = O.decode16(to_bits(y), dtype)
+    for b in range(2):
+        assert rel_l2(got[b], O.round16(O.sparse_project_gather(h[b], idx[b], W), dtype)) <= REL_L2_TOL

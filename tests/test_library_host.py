@@ -1,0 +1,84 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces, and rejects invalid arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "larosa.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2507_01299_amd import api, build
+    if not os.path.exists(api.LIB_PATH):
+        build.build_library()
+    return api.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(larosa_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"larosa_rotate", "larosa_topk", "larosa_sparse_gemv", "larosa_layer_forward"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings_and_version(lib):
+    from paper_2507_01299_amd import api
+    assert api.version() >= 100
+    seen = {api.status_string(s) for s in (0, -1, -2, -3, -4, -99)}
+    assert len(seen) == 6 and api.status_string(0) == "ok"
+
+
+def test_workspace_bytes_is_pure_and_monotone(lib):
+    a = lib.larosa_workspace_bytes(1, 4096, 4096, 2457)
+    b = lib.larosa_workspace_bytes(1, 4096, 22016, 2457)
+    c = lib.larosa_workspace_bytes(4, 4096, 22016, 2457)
+    assert 0 < a <= b < c and a % 256 == 0
+    assert lib.larosa_workspace_bytes(0, 1, 1, 1) == 0
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    from paper_2507_01299_amd import api
+    null = None
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: checks fail first
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.larosa_sparse_gemv(null, fake, fake, fake, 1, 64, 64, 8, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 64, 0, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 64, 65, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 60, 8, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(odd, fake, fake, fake, 1, 64, 64, 8, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 64, 8, 7, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 64, 8, 0, fake, 16, null) == api.EWORKSPACE
+    assert lib.larosa_sparse_gemv(fake, fake, fake, fake, 1, 64, 64, 8, 0, null, 0, null) == api.EWORKSPACE
+    assert lib.larosa_topk(fake, 1, 64, 0, fake, null, 0, null, 0, null) == api.EINVAL
+    assert lib.larosa_topk(fake, 1, 64, 65, fake, null, 0, null, 0, null) == api.EINVAL
+    assert lib.larosa_topk(fake, 1, 65536, 8, fake, null, 0, null, 0, null) == api.EUNSUPPORTED
+    assert lib.larosa_rotate(fake, null, fake, 1, 64, 0, fake, 1 << 20, null) == api.EINVAL
+    assert lib.larosa_workspace_init(null, 1 << 20, null) == api.EWORKSPACE
+    assert lib.larosa_set_tuning(99, 1) == api.EINVAL
+
+
+def test_layer_struct_validation(lib):
+    from paper_2507_01299_amd import api
+    L = api._Layer(256, 256, 128, 704, 32, 100, 100, 100, 300, 0x1000, 0x1000, 0x1000, 0x1000,
+                   None, None, None, None, None, -1.0, 0, 0)
+    n = lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2)
+    assert n > 0
+    L.K4 = 705
+    assert lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2) == 0
+    L.K4 = 300
+    L.head_dim = 48
+    assert lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2) == 0
+    L.head_dim = 32
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.larosa_layer_forward(ctypes.byref(L), fake, fake, 1, None, fake, n, None) == api.EINVAL  # x_out aliases x
+    assert lib.larosa_layer_forward(ctypes.byref(L), fake, ctypes.c_void_p(0x2000), 1, None, fake, 16, None) == api.EWORKSPACE
