@@ -10,8 +10,9 @@ using namespace larosa;
 
 namespace {
 
-constexpr size_t kCounterSlots = 16384;                       // u32 arrival counters at the head of a workspace
-constexpr size_t kCounterBytes = kCounterSlots * sizeof(unsigned);
+constexpr size_t kCounterSlots = 4096;                        // arrival counters at the head of a workspace
+constexpr size_t kCounterWords = kCounterSlots * kCounterStride;
+constexpr size_t kCounterBytes = kCounterWords * sizeof(unsigned);
 constexpr int kMaxTopkD = 32768;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -85,7 +86,7 @@ size_t larosa_workspace_bytes(int B, int d_in_max, int d_out_max, int K_max) {
 
 int larosa_workspace_init(void* ws, size_t ws_bytes, void* stream) {
   if (!ws || !aligned(ws, 256) || ws_bytes < kCounterBytes) return LAROSA_EWORKSPACE;
-  return launch_fill_u32(static_cast<unsigned*>(ws), kCounterSlots, 0u, static_cast<hipStream_t>(stream)) ==
+  return launch_fill_u32(static_cast<unsigned*>(ws), kCounterWords, 0u, static_cast<hipStream_t>(stream)) ==
                  hipSuccess
              ? LAROSA_OK
              : LAROSA_EHIP;

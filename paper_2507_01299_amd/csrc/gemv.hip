@@ -107,42 +107,83 @@ __global__ __launch_bounds__(CW* RW * 64) void gemv_rows_kernel(GemvArgs a) {
       }
     }
 
-    // cross-workgroup sum: the last workgroup to arrive at strip s adds all partials in order
+    // cross-workgroup sum: the last workgroup to arrive at strip s adds all partials in a fixed order
     const int g_first = (s * K) / chunk;
     const int g_last = ((s + 1) * K - 1) / chunk;
     const int n_s = g_last - g_first + 1;
     bool last = (n_s == 1);
     if (n_s > 1) {
-      float* slot = a.partial + ((static_cast<size_t>(b) * a.G + g) * 2 + seg) * SC + cw * 512 + lane * 8;
+      // Partials travel as relaxed agent-scope 64-bit atomics: such accesses are coherent across
+      // the chip's L2 slices by themselves, so no cache write-back / invalidate is needed (a
+      // release/acquire fence pair per workgroup costs far more than the whole mat-vec here).
+      // Order: every lane waits for its stores to complete, the workgroup barrier joins the lanes,
+      // then one lane bumps the strip's arrival counter; the workgroup that observes the last
+      // arrival therefore reads completed stores.  Slot layout [4][CW*64] of float pairs keeps
+      // each store instruction one contiguous 512-byte run per wave.
+      unsigned long long* slot =
+          reinterpret_cast<unsigned long long*>(a.partial + ((static_cast<size_t>(b) * a.G + g) * 2 + seg) * SC);
+      // one counter per 256 bytes: arrivals at different strips must not share a cache line
+      unsigned* ctr = a.counters + (static_cast<size_t>(b) * a.nstrips + s) * kCounterStride;
       if (rw == 0) {
-        *reinterpret_cast<float4*>(slot) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        *reinterpret_cast<float4*>(slot + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(acc[2 * k])) |
+                                       (static_cast<unsigned long long>(__float_as_uint(acc[2 * k + 1])) << 32);
+          __hip_atomic_store(slot + k * (CW * 64) + cw * 64 + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
       }
-      __threadfence();
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      unsigned* ctr = a.counters + static_cast<size_t>(b) * a.nstrips + s;
       if (threadIdx.x == 0) {
-        const unsigned old = atomicAdd(ctr, 1u);
+        const unsigned old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (old == static_cast<unsigned>(n_s - 1)) ? 1 : 0;
       }
       __syncthreads();
       last = (s_last != 0);
       if (last) {
-        __threadfence();
-        if (rw == 0) {
+        // row-wave rw adds partials g_first+rw, g_first+rw+RW, ... (kBatch in flight at a time);
+        // the RW sub-sums are then added in wave order through LDS: the order never changes.
+        constexpr int kBatch = 8;
 #pragma unroll
-          for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-          for (int gg = g_first; gg <= g_last; ++gg) {
-            const int sg = ((gg * chunk) / K != s) ? 1 : 0;
-            const float* p =
-                a.partial + ((static_cast<size_t>(b) * a.G + gg) * 2 + sg) * SC + cw * 512 + lane * 8;
-            const float4 p0 = *reinterpret_cast<const float4*>(p);
-            const float4 p1 = *reinterpret_cast<const float4*>(p + 4);
-            acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
-            acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w;
+        for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+        for (int gg = g_first + rw; gg <= g_last; gg += kBatch * RW) {
+          unsigned long long v[kBatch][4];
+#pragma unroll
+          for (int q = 0; q < kBatch; ++q) {
+            const int g2 = min(gg + q * RW, g_last);
+            const int sg = ((g2 * chunk) / K != s) ? 1 : 0;
+            const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
+                a.partial + ((static_cast<size_t>(b) * a.G + g2) * 2 + sg) * SC);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              v[q][k] = __hip_atomic_load(p + k * (CW * 64) + cw * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+          for (int q = 0; q < kBatch; ++q) {
+            if (gg + q * RW <= g_last) {
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                acc[2 * k] += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
+                acc[2 * k + 1] += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
+              }
+            }
           }
         }
-        if (threadIdx.x == 0) *ctr = 0u;
+        if (threadIdx.x == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (RW > 1) {
+          __syncthreads();                 // the first LDS reduction has been consumed by every wave
+          if (rw > 0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) red[rw - 1][k][cw * 64 + lane] = acc[k];
+          }
+          __syncthreads();
+          if (rw == 0) {
+            for (int r = 0; r < RW - 1; ++r) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) acc[k] += red[r][k][cw * 64 + lane];
+            }
+          }
+        }
       }
     }
 

@@ -19,7 +19,7 @@ struct GemvArgs {
   // [g*chunk, (g+1)*chunk).  chunk <= K, so a workgroup touches at most two strips.
   int chunk, G, nstrips;
   float* partial;             // [B][G][2][strip_cols] fp32 partial sums
-  unsigned* counters;         // [B][nstrips] arrival counters, zero on entry and on exit
+  unsigned* counters;         // [B][nstrips] arrival counters (kCounterStride apart), zero on entry and on exit
   // epilogue
   const uint16_t* coef_scale; // [d_in] or nullptr: multiplies the coefficient (pre-norm scale)
   const uint16_t* rms_src;    // [B, d_in] or nullptr: result is multiplied by 1/sqrt(mean(rms_src^2)+eps)
@@ -28,13 +28,15 @@ struct GemvArgs {
   uint16_t* y_pre;            // [B, d_out] or nullptr: receives R(acc) when a residual is added
 };
 
+constexpr int kCounterStride = 64;   // in 32-bit words: one arrival counter per 256 bytes
+
 struct GemvPlan {
   int strip_cols, nstrips, chunk, G;
   size_t partial_floats;      // per token
 };
 
 struct Tuning {
-  int g_target = 1024;        // target workgroups per launch
+  int g_target = 512;         // target workgroups per launch (two resident per CU)
   int min_rows = 8;           // minimum row-strips per workgroup
   int variant = 0;            // kernel shape variant
 };

@@ -161,7 +161,7 @@ def test_sparse_gemv_every_launch_shape(api, variant, g_target, min_rows):
         api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
         torch.cuda.synchronize()
     finally:
-        api.set_tuning(2, 0); api.set_tuning(0, 1024); api.set_tuning(1, 8)
+        api.set_tuning(2, 0); api.set_tuning(0, 512); api.set_tuning(1, 8)
     W = O.decode16(wb, dtype)
     got = O.decode16(to_bits(y), dtype)
     for b in range(2):
