@@ -65,8 +65,8 @@ int larosa_workspace_init(void* ws, size_t ws_bytes, void* stream);
  *   h[b,i] = sum_j x[b,j] * Q[j,i]
  * x [B,d], Q [d,d] row-major (row j = input channel j; column i = i-th principal direction),
  * h [B,d].  Also serves the residual adapter x (Q_l^T Q_{l+1}) (Sec. 4.2) and, being a dense
- * mat-vec over an input-channel-major matrix, the dense comparator.
- * `Q` may be rectangular for that last use: pass d_out != d through larosa_dense_gemv. */
+ * mat-vec over an input-channel-major matrix, the dense comparator (larosa_dense_gemv is the
+ * same operation with a rectangular matrix). */
 int larosa_rotate(const void* x, const void* Q, void* h, int B, int d, larosa_dtype t,
                   void* ws, size_t ws_bytes, void* stream);
 
@@ -135,9 +135,11 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B);
 int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int B,
                          const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
 
-/* Kernel launch tuning for experiments (host state, not thread-safe): key 0 = target number
- * of workgroups of the row-streaming kernels, key 1 = minimum rows per workgroup,
- * key 2 = kernel variant.  Returns LAROSA_EINVAL for an unknown key or a value out of range. */
+/* Kernel launch tuning for experiments (host state, not thread-safe; set it before sizing a
+ * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
+ * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,
+ * 2: 4), key 3 = decoder layer with the Top-K fused into the projection kernels (1, default) or
+ * as separate kernels (0).  Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 
 #ifdef __cplusplus

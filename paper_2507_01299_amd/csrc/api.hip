@@ -20,9 +20,9 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool dtype_ok(int t) { return t == LAROSA_F16 || t == LAROSA_BF16; }
 
 size_t gemv_partial_bytes_bound(int B, int d_out_max) {
-  const int sc = gemv_strip_cols();
+  const int sc = 512;
   const long nstrips = (d_out_max + sc - 1) / sc;
-  long G = tuning().g_target;
+  long G = tuning().g_target > 0 ? tuning().g_target : 512;
   if (G < nstrips) G = nstrips;
   return static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * sc * sizeof(float);
 }
@@ -52,6 +52,20 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   a.counters = static_cast<unsigned*>(ws);
   a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
   return launch_gemv(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
+// One launch of the projection kernel with the Top-K prologue.
+int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
+  const GemvPlan p = plan_fused(a.g.d_out, a.g.K);
+  if (static_cast<size_t>(a.g.B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  const size_t need = kCounterBytes + static_cast<size_t>(a.g.B) * p.partial_floats * sizeof(float);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  a.g.chunk = p.chunk;
+  a.g.G = p.G;
+  a.g.nstrips = p.nstrips;
+  a.g.counters = static_cast<unsigned*>(ws);
+  a.g.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  return launch_fused(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
 int check_gemv_shapes(int B, int d_in, int d_out, int K) {
@@ -164,8 +178,15 @@ static int check_layer(const larosa_layer* L, int B) {
 static int max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 
 static size_t layer_gemv_ws(const larosa_layer* L, int B) {
-  return larosa_workspace_bytes(B, max3(L->d, L->d_q, L->d_ff), max3(L->d_q + 2 * L->d_kv, 2 * L->d_ff, L->d),
-                                max3(L->d, L->d_q, L->d_ff));
+  size_t s = larosa_workspace_bytes(B, max3(L->d, L->d_q, L->d_ff), max3(L->d_q + 2 * L->d_kv, 2 * L->d_ff, L->d),
+                                    max3(L->d, L->d_q, L->d_ff));
+  const GemvPlan plans[] = {plan_fused(L->d_q + 2 * L->d_kv, L->K1), plan_fused(L->d, L->K2),
+                            plan_fused(2 * L->d_ff, L->K3), plan_fused(L->d, L->K4)};
+  for (const GemvPlan& p : plans) {
+    const size_t need = round_up(kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float), 256);
+    if (need > s) s = need;
+  }
+  return s;
 }
 
 size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
@@ -260,6 +281,39 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     return run_gemv(a, bf, ws, gws, st);
   };
 
+  if (tuning().fused) {
+    // Top-K fused into the projections: 4 projection kernels (+ one rotation each when Q is given)
+    auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
+                     const uint16_t* residual, uint16_t* y_pre, uint16_t* h_out, int32_t* idx_out,
+                     const void* nscale) -> int {
+      FusedArgs a{};
+      a.g.W = static_cast<const uint16_t*>(W);
+      a.g.y = y;
+      a.g.d_in = d_in; a.g.d_out = d_out; a.g.K = K; a.g.B = B;
+      a.g.residual = residual; a.g.y_pre = y_pre;
+      a.src_mode = mode; a.src = src;
+      a.d_q = d_q; a.d_kv = d_kv; a.head_dim = L->head_dim;
+      a.group = (d_q / L->head_dim) / (d_kv / L->head_dim);
+      a.norm_scale = static_cast<const uint16_t*>(nscale); a.norm_eps = L->rms_eps;
+      a.h_out = h_out; a.idx_out = idx_out;
+      return run_fused(a, bf, ws, gws, st);
+    };
+    auto first = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* h, void* h_traced, const void* W,
+                     uint16_t* y, int d_out, int K, int32_t* idx_traced) -> int {
+      if (Q) {
+        if (int rc = block_input(src, Q, scale, h)) return rc;
+        return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr);
+      }
+      return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
+                   static_cast<uint16_t*>(h_traced), idx_traced, scale);
+    };
+    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1));
+    LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, x, static_cast<uint16_t*>(T.o),
+                     static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
+    LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3));
+    LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, x1, static_cast<uint16_t*>(T.down),
+                     static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
+  } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
   LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
   LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, st));
@@ -274,6 +328,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
   LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, st));
   LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+  }
   // residual adapter
   if (L->adapter) {
     GemvArgs a{};
@@ -292,7 +347,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
 int larosa_set_tuning(int key, int value) {
   switch (key) {
     case 0:
-      if (value < 1 || value > 4096) return LAROSA_EINVAL;
+      if (value < 0 || value > 4096) return LAROSA_EINVAL;
       tuning().g_target = value;
       return LAROSA_OK;
     case 1:
@@ -300,8 +355,12 @@ int larosa_set_tuning(int key, int value) {
       tuning().min_rows = value;
       return LAROSA_OK;
     case 2:
-      if (value < 0 || value > 5) return LAROSA_EINVAL;
+      if (value < 0 || value > 2) return LAROSA_EINVAL;
       tuning().variant = value;
+      return LAROSA_OK;
+    case 3:
+      if (value < 0 || value > 1) return LAROSA_EINVAL;
+      tuning().fused = value;
       return LAROSA_OK;
     default:
       return LAROSA_EINVAL;

@@ -36,15 +36,33 @@ struct GemvPlan {
 };
 
 struct Tuning {
-  int g_target = 512;         // target workgroups per launch (two resident per CU)
+  int g_target = 0;           // target workgroups per launch; 0 = automatic (256 or 512)
   int min_rows = 8;           // minimum row-strips per workgroup
-  int variant = 0;            // kernel shape variant
+  int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
+  int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
 };
 Tuning& tuning();
 
 GemvPlan plan_gemv(int d_out, int K);
-int gemv_strip_cols();
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
+
+// Column-sparse projection with the Top-K select fused into its prologue: the kept list is
+// built inside every workgroup from the block's input vector.
+enum : int { kSrcPlain = 0, kSrcGqa = 1, kSrcSilu = 2, kSrcNorm = 3 };
+constexpr int kFusedChunkMax = 2048;   // (strip, rank) pairs per workgroup that fit its LDS list
+struct FusedArgs {
+  GemvArgs g;                 // W, y, sizes, work split, workspace, epilogue; g.h and g.idx unused
+  int src_mode;               // where the input vector of width g.d_in comes from:
+  const uint16_t* src;        //   kSrcPlain: [B, d_in];  kSrcNorm: x [B, d_in] to be RMS-normed;
+                              //   kSrcGqa: q|k|v [B, d_q+2d_kv];  kSrcSilu: gate|up [B, 2 d_in]
+  int d_q, d_kv, head_dim, group;
+  const uint16_t* norm_scale; // kSrcNorm: [d_in] or nullptr
+  float norm_eps;
+  uint16_t* h_out;            // nullable: receives the input vector [B, d_in]
+  int32_t* idx_out;           // nullable: receives the kept indices [B, K], ascending
+};
+GemvPlan plan_fused(int d_out, int K);
+hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 
 // Top-K select over stored 16-bit magnitudes, one workgroup per token.
 hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, hipStream_t s);

@@ -1,0 +1,149 @@
+// Workgroup-level radix select for the Top-K sparsifier S_k (Sec. 4.3, Eq. 8), shared by the
+// stand-alone Top-K kernel and the Top-K prologue of the fused projection kernel.
+//
+// The ordering key is the stored 16-bit pattern with the sign cleared (15 bits, unsigned), so
+// the selection is pure integer work and identical for binary16 and bfloat16.  Lane t owns the
+// contiguous elements [t*E, (t+1)*E) and keeps them in registers through all phases:
+//   1. 256-bin histogram of the top 8 key bits (one LDS copy per wave to spread atomics);
+//      suffix sums from the top locate the bin holding the K-th largest key;
+//   2. 128-bin histogram of the low 7 bits inside that bin gives the threshold key T and
+//      r = K - #{key > T}, the number of threshold ties to keep;
+//   3. block prefix sums of the ">T" and "==T" counts give every lane the number of kept
+//      elements before its own, so an index-ordered compaction keeps every key > T and the first
+//      r keys == T: ascending indices and the lower-index tie rule with no sort.
+#pragma once
+#include "numeric.hpp"
+
+namespace larosa {
+
+template <int NW>
+struct TopkShared {
+  unsigned hist_w[NW][256];
+  unsigned hist[256];
+  unsigned wave_tot[NW];
+  int bin;
+  unsigned above;
+};
+
+// Over bins visited from the highest down, find the first bin at which the running count
+// reaches `need`.  Executed by one wave; each lane covers NB/64 bins.
+template <int NB>
+__device__ __forceinline__ void locate_bin(const unsigned* hist, unsigned need, int lane, int* out_bin,
+                                           unsigned* out_above) {
+  constexpr int PER = NB / 64;
+  unsigned c[PER];
+  unsigned local = 0;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    c[q] = hist[NB - 1 - (lane * PER + q)];   // position lane*PER+q counts from the top bin
+    local += c[q];
+  }
+  const unsigned incl = wave_scan_inclusive(local, lane);
+  unsigned run = incl - local;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const unsigned before = run;
+    run += c[q];
+    if (before < need && run >= need) {
+      *out_bin = NB - 1 - (lane * PER + q);
+      *out_above = before;
+    }
+  }
+}
+
+// Selection state of one lane after block_select.
+struct TopkLane {
+  unsigned T;          // threshold key
+  unsigned r;          // number of keys == T to keep (>= 1)
+  unsigned gt_before;  // kept-by-magnitude elements before this lane's first element
+  unsigned eq_before;  // threshold ties before this lane's first element
+};
+
+// raw[q] (q < nvalid) are this lane's stored 16-bit values.  Every lane of the NW-wave workgroup
+// must call this.  1 <= K <= total number of valid elements <= 32768.
+template <int NW, int E>
+__device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int nvalid, int K, TopkShared<NW>& sm) {
+  constexpr int NT = NW * 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  unsigned* flat = &sm.hist_w[0][0];
+
+  for (int i = tid; i < NW * 256; i += NT) flat[i] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < E; ++q)
+    if (q < nvalid) atomicAdd(&sm.hist_w[wave][(raw[q] & 0x7FFFu) >> 7], 1u);
+  __syncthreads();
+  if (tid < 256) {
+    unsigned s = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += sm.hist_w[w][tid];
+    sm.hist[tid] = s;
+  }
+  __syncthreads();
+  if (wave == 0) locate_bin<256>(sm.hist, static_cast<unsigned>(K), lane, &sm.bin, &sm.above);
+  __syncthreads();
+  const int bin1 = sm.bin;
+  const unsigned above1 = sm.above;
+  __syncthreads();
+
+  for (int i = tid; i < NW * 128; i += NT) flat[i] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < E; ++q) {
+    const unsigned key = raw[q] & 0x7FFFu;
+    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&flat[wave * 128 + (key & 127u)], 1u);
+  }
+  __syncthreads();
+  if (tid < 128) {
+    unsigned s = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += flat[w * 128 + tid];
+    sm.hist[tid] = s;
+  }
+  __syncthreads();
+  if (wave == 0) locate_bin<128>(sm.hist, static_cast<unsigned>(K) - above1, lane, &sm.bin, &sm.above);
+  __syncthreads();
+  TopkLane out;
+  out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(sm.bin);
+  out.r = static_cast<unsigned>(K) - (above1 + sm.above);
+
+  unsigned n_gt = 0, n_eq = 0;
+#pragma unroll
+  for (int q = 0; q < E; ++q) {
+    const unsigned key = raw[q] & 0x7FFFu;
+    if (q < nvalid) {
+      n_gt += (key > out.T) ? 1u : 0u;
+      n_eq += (key == out.T) ? 1u : 0u;
+    }
+  }
+  const unsigned packed = n_gt | (n_eq << 16);          // each total <= 32768: no carry between halves
+  const unsigned incl = wave_scan_inclusive(packed, lane);
+  if (lane == 63) sm.wave_tot[wave] = incl;
+  __syncthreads();
+  unsigned prefix = incl - packed;
+  for (int w = 0; w < wave; ++w) prefix += sm.wave_tot[w];
+  out.gt_before = prefix & 0xFFFFu;
+  out.eq_before = prefix >> 16;
+  return out;
+}
+
+// Visit this lane's elements in index order; emit(q, pos) is called for every kept element with
+// its rank pos in the ascending kept list.
+template <int E, typename F>
+__device__ __forceinline__ void for_each_kept(const uint16_t (&raw)[E], int nvalid, TopkLane st, F emit) {
+#pragma unroll
+  for (int q = 0; q < E; ++q) {
+    if (q < nvalid) {
+      const unsigned key = raw[q] & 0x7FFFu;
+      const bool gt = key > st.T;
+      const bool eq = key == st.T;
+      if (gt || (eq && st.eq_before < st.r)) emit(q, st.gt_before + min(st.eq_before, st.r));
+      st.gt_before += gt ? 1u : 0u;
+      st.eq_before += eq ? 1u : 0u;
+    }
+  }
+}
+
+}  // namespace larosa

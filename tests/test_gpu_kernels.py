@@ -145,8 +145,8 @@ def test_sparse_gemv_full_K_equals_dense_gemv_and_is_deterministic(api, ws):
     assert rel_l2(O.decode16(to_bits(y1), dtype), want) <= REL_L2_TOL
 
 
-@pytest.mark.parametrize("variant,g_target,min_rows", [(0, 64, 4), (1, 2048, 1), (2, 256, 16), (3, 1024, 8),
-                                                        (4, 512, 2), (5, 4096, 64)])
+@pytest.mark.parametrize("variant,g_target,min_rows", [(0, 64, 4), (1, 2048, 1), (2, 256, 16), (0, 1024, 8),
+                                                        (2, 512, 2), (1, 4096, 64)])
 def test_sparse_gemv_every_launch_shape(api, variant, g_target, min_rows):
     """Each kernel shape variant and work split gives the same answer (within rounding order)."""
     dtype, d_in, d_out, K = "bf16", 1536, 3080, 777
@@ -161,7 +161,7 @@ def test_sparse_gemv_every_launch_shape(api, variant, g_target, min_rows):
         api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
         torch.cuda.synchronize()
     finally:
-        api.set_tuning(2, 0); api.set_tuning(0, 512); api.set_tuning(1, 8)
+        api.set_tuning(2, 0); api.set_tuning(0, 0); api.set_tuning(1, 8)
     W = O.decode16(wb, dtype)
     got = O.decode16(to_bits(y), dtype)
     for b in range(2):

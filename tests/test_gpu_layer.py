@@ -32,10 +32,18 @@ def _run_layer(api, case, B, seed, trace=True):
     return xb, out, tr, dl, ws
 
 
+@pytest.fixture(params=[1, 0], ids=["fused", "separate"])
+def fused_mode(api, request):
+    """Run the layer with the Top-K fused into the projection kernels and as separate kernels."""
+    api.set_tuning(3, request.param)
+    yield request.param
+    api.set_tuning(3, 1)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("adapter", [False, True])
-def test_tiny_layer_every_stage(api, dtype, adapter):
-    print(f"tiny layer dtype={dtype} adapter={adapter}", flush=True)
+def test_tiny_layer_every_stage(api, fused_mode, dtype, adapter):
+    print(f"tiny layer dtype={dtype} adapter={adapter} fused={fused_mode}", flush=True)
     shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, dtype)
     case = cases.build_block_layer(shape, 0.4, seed=51, n_cal=1024, with_adapter=adapter)
     xb, out, tr, dl, ws = _run_layer(api, case, 3, seed=8)
@@ -48,7 +56,17 @@ def test_tiny_layer_every_stage(api, dtype, adapter):
     assert np.array_equal(to_bits(out), to_bits(out2))
 
 
-def test_folded_stack_tiny(api):
+def test_ragged_layer_shapes(api, fused_mode):
+    """Widths that are not multiples of the 512-column strip or of the per-lane element run, GQA
+    with 4 query heads per value head, K values at both extremes."""
+    shape = synth.LayerShape("ragged", 328, 384, 96, 1000, 24, "bf16")
+    for Ks in ((1, 384, 327, 999), (328, 1, 1, 1), (200, 100, 150, 613)):
+        case = cases.build_block_layer(shape, 0.4, seed=71, n_cal=768, Ks=Ks)
+        xb, out, tr, dl, ws = _run_layer(api, case, 2, seed=4)
+        check_layer_trace(case.layer, xb, tr, out)
+
+
+def test_folded_stack_tiny(api, fused_mode):
     """Deployed form: no explicit rotations, per-layer adapters, x carried in the layer basis."""
     shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "f16")
     layers, bits, Qs, Ws, src = cases.build_folded_stack(shape, 4, 0.4, seed=61, n_cal=1024)
