@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--detail", default=None, help="also write the full report to this JSON file")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="larosa_set_tuning(KEY, VALUE) before anything is sized (experiments)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -70,6 +72,9 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(2)
     api.lib()
+    for kv in args.tune:
+        k, v = kv.split("=")
+        api.set_tuning(int(k), int(v))
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
     shape = synth.SHAPES[cfg["shape"]]

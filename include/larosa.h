@@ -139,7 +139,8 @@ int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int 
  * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
  * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,
  * 2: 4), key 3 = decoder layer with the Top-K fused into the projection kernels (1, default) or
- * as separate kernels (0).  Returns LAROSA_EINVAL for an unknown key or a value out of range. */
+ * as separate kernels (0), key 4 = row-waves per workgroup of that fused kernel (8 or 16).
+ * Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 
 #ifdef __cplusplus

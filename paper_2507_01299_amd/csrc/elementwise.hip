@@ -32,7 +32,7 @@ __global__ void silu_mul_kernel(const uint16_t* __restrict__ gu, uint16_t* __res
   unpack8<T>(*reinterpret_cast<const uint4*>(gu + row + i), g);
   unpack8<T>(*reinterpret_cast<const uint4*>(gu + row + d_ff + i), u);
 #pragma unroll
-  for (int k = 0; k < 8; ++k) o[k] = (g[k] / (1.0f + expf(-g[k]))) * u[k];
+  for (int k = 0; k < 8; ++k) o[k] = silu_f32(g[k]) * u[k];
   *reinterpret_cast<uint4*>(h4 + static_cast<size_t>(b) * d_ff + i) = pack8<T>(o);
 }
 

@@ -15,14 +15,12 @@ namespace larosa {
 
 namespace {
 
-constexpr int kFusedRW = 8;
-constexpr int kFusedThreads = kFusedRW * 64;
-
-template <typename T, int NV>   // NV 16-byte groups (8 elements each) per lane
-__global__ __launch_bounds__(kFusedThreads) void fused_topk_gemv_kernel(FusedArgs a) {
-  constexpr int E = NV * 8;
-  __shared__ TopkShared<kFusedRW> tk;
-  __shared__ GemvShared<kFusedRW> sh;
+template <typename T, int RW, int NV>   // RW row-waves; NV 8-byte groups (4 elements each) per lane
+__global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
+  constexpr int E = NV * 4;
+  constexpr int kFusedRW = RW;
+  __shared__ TopkShared<RW> tk;
+  __shared__ GemvShared<RW> sh;
   __shared__ int lst_idx[kFusedChunkMax];
   __shared__ float lst_val[kFusedChunkMax];
 
@@ -40,30 +38,32 @@ __global__ __launch_bounds__(kFusedThreads) void fused_topk_gemv_kernel(FusedArg
   uint16_t raw[E];
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
-    const int i = base + q * 8;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    const int i = base + q * 4;
+    uint2 v = make_uint2(0u, 0u);
     if (i < d_in) {
       if (a.src_mode == kSrcGqa) {
         // context-length-1 attention: query head i/head_dim outputs the value head of its group
         const int head = i / a.head_dim;
         const int src = (head / a.group) * a.head_dim + (i - head * a.head_dim);
-        v = *reinterpret_cast<const uint4*>(a.src + static_cast<size_t>(b) * (a.d_q + 2 * a.d_kv) + a.d_q + a.d_kv + src);
+        v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * (a.d_q + 2 * a.d_kv) + a.d_q + a.d_kv + src);
       } else if (a.src_mode == kSrcSilu) {
         const uint16_t* row = a.src + static_cast<size_t>(b) * 2 * d_in;
-        float gt[8], up[8], o[8];
-        unpack8<T>(*reinterpret_cast<const uint4*>(row + i), gt);
-        unpack8<T>(*reinterpret_cast<const uint4*>(row + d_in + i), up);
+        const uint2 gv = *reinterpret_cast<const uint2*>(row + i);
+        const uint2 uv = *reinterpret_cast<const uint2*>(row + d_in + i);
+        float gt[4], up[4];
+        T::unpack2(gv.x, gt[0], gt[1]); T::unpack2(gv.y, gt[2], gt[3]);
+        T::unpack2(uv.x, up[0], up[1]); T::unpack2(uv.y, up[2], up[3]);
+        uint16_t o[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) o[k] = (gt[k] / (1.0f + expf(-gt[k]))) * up[k];
-        v = pack8<T>(o);
+        for (int k = 0; k < 4; ++k) o[k] = T::from_f32(silu_f32(gt[k]) * up[k]);
+        v.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
+        v.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
       } else {
-        v = *reinterpret_cast<const uint4*>(a.src + static_cast<size_t>(b) * d_in + i);
+        v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * d_in + i);
       }
     }
-    raw[q * 8 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu); raw[q * 8 + 1] = static_cast<uint16_t>(v.x >> 16);
-    raw[q * 8 + 2] = static_cast<uint16_t>(v.y & 0xFFFFu); raw[q * 8 + 3] = static_cast<uint16_t>(v.y >> 16);
-    raw[q * 8 + 4] = static_cast<uint16_t>(v.z & 0xFFFFu); raw[q * 8 + 5] = static_cast<uint16_t>(v.z >> 16);
-    raw[q * 8 + 6] = static_cast<uint16_t>(v.w & 0xFFFFu); raw[q * 8 + 7] = static_cast<uint16_t>(v.w >> 16);
+    raw[q * 4 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu); raw[q * 4 + 1] = static_cast<uint16_t>(v.x >> 16);
+    raw[q * 4 + 2] = static_cast<uint16_t>(v.y & 0xFFFFu); raw[q * 4 + 3] = static_cast<uint16_t>(v.y >> 16);
   }
   if (a.src_mode == kSrcNorm) {
     // h = R(x * rsqrt(mean(x^2) + eps) * scale)
@@ -92,14 +92,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_topk_gemv_kernel(FusedArg
   if (a.h_out && g == 0) {
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
-      const int i = base + q * 8;
+      const int i = base + q * 4;
       if (i < d_in) {
-        uint4 v;
-        v.x = raw[q * 8 + 0] | (static_cast<uint32_t>(raw[q * 8 + 1]) << 16);
-        v.y = raw[q * 8 + 2] | (static_cast<uint32_t>(raw[q * 8 + 3]) << 16);
-        v.z = raw[q * 8 + 4] | (static_cast<uint32_t>(raw[q * 8 + 5]) << 16);
-        v.w = raw[q * 8 + 6] | (static_cast<uint32_t>(raw[q * 8 + 7]) << 16);
-        *reinterpret_cast<uint4*>(a.h_out + static_cast<size_t>(b) * d_in + i) = v;
+        uint2 v;
+        v.x = raw[q * 4 + 0] | (static_cast<uint32_t>(raw[q * 4 + 1]) << 16);
+        v.y = raw[q * 4 + 2] | (static_cast<uint32_t>(raw[q * 4 + 3]) << 16);
+        *reinterpret_cast<uint2*>(a.h_out + static_cast<size_t>(b) * d_in + i) = v;
       }
     }
   }
@@ -113,18 +111,22 @@ __global__ __launch_bounds__(kFusedThreads) void fused_topk_gemv_kernel(FusedArg
   const int nA = min(K - tA0, f1 - f0);   // ranks [tA0, tA0+nA) of strip sA
   const int nB = (f1 - f0) - nA;          // ranks [0, nB) of strip sA+1; nB <= tA0, so the two never overlap
   int32_t* idx_out = (a.idx_out && g == 0) ? a.idx_out + static_cast<size_t>(b) * K : nullptr;
-  for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned upos) {
-    const int pos = static_cast<int>(upos);
-    if (pos >= K) return;                 // never taken; keeps a stray rank out of the lists
-    if (idx_out) idx_out[pos] = base + q;
-    int e = -1;
-    if (pos >= tA0 && pos < tA0 + nA) e = pos - tA0;
-    else if (pos < nB) e = nA + pos;
-    if (e >= 0) {
-      lst_idx[e] = base + q;
-      lst_val[e] = T::to_f32(raw[q]);
-    }
-  });
+  // only lanes whose ranks meet this workgroup's two rank ranges (a few percent) walk their elements
+  const int p0 = static_cast<int>(st.first_rank()), p1 = static_cast<int>(st.end_rank());
+  if (idx_out || (p0 < tA0 + nA && p1 > tA0) || p0 < nB) {
+    for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned upos) {
+      const int pos = static_cast<int>(upos);
+      if (pos >= K) return;                 // never taken; keeps a stray rank out of the lists
+      if (idx_out) idx_out[pos] = base + q;
+      int e = -1;
+      if (pos >= tA0 && pos < tA0 + nA) e = pos - tA0;
+      else if (pos < nB) e = nA + pos;
+      if (e >= 0) {
+        lst_idx[e] = base + q;
+        lst_val[e] = T::to_f32(raw[q]);
+      }
+    });
+  }
   __syncthreads();
 
   // ---- stream the kept rows of the (at most two) segments
@@ -154,24 +156,45 @@ __global__ __launch_bounds__(kFusedThreads) void fused_topk_gemv_kernel(FusedArg
   }
 }
 
-template <typename T>
+template <typename T, int RW>
 hipError_t launch_nv(const FusedArgs& a, hipStream_t st) {
-  dim3 grid(a.g.G, a.g.B), block(kFusedThreads);
-  const int nv = (a.g.d_in + kFusedThreads * 8 - 1) / (kFusedThreads * 8);
-  if (nv <= 1) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 1>), grid, block, 0, st, a);
-  else if (nv <= 2) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 2>), grid, block, 0, st, a);
-  else if (nv <= 3) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 3>), grid, block, 0, st, a);
-  else if (nv <= 4) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 4>), grid, block, 0, st, a);
-  else if (nv <= 6) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 6>), grid, block, 0, st, a);
-  else if (nv <= 8) hipLaunchKernelGGL((fused_topk_gemv_kernel<T, 8>), grid, block, 0, st, a);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
+  dim3 grid(a.g.G, a.g.B), block(RW * 64);
+  const int nv = (a.g.d_in + RW * 64 * 4 - 1) / (RW * 64 * 4);
+#define LAROSA_FUSED_CASE(N) \
+  if (nv <= N) { hipLaunchKernelGGL((fused_topk_gemv_kernel<T, RW, N>), grid, block, 0, st, a); return hipGetLastError(); }
+  LAROSA_FUSED_CASE(1)
+  LAROSA_FUSED_CASE(2)
+  LAROSA_FUSED_CASE(3)
+  LAROSA_FUSED_CASE(4)
+  LAROSA_FUSED_CASE(6)
+  LAROSA_FUSED_CASE(8)
+  if (RW == 8) {
+    LAROSA_FUSED_CASE(12)
+    LAROSA_FUSED_CASE(16)
+  }
+#undef LAROSA_FUSED_CASE
+  return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t launch_rw(const FusedArgs& a, hipStream_t st) {
+  return fused_row_waves() == 16 ? launch_nv<T, 16>(a, st) : launch_nv<T, 8>(a, st);
 }
 
 }  // namespace
 
+int fused_row_waves() { return tuning().fused_rw == 16 ? 16 : 8; }
+
 GemvPlan plan_fused(int d_out, int K) {
   GemvPlan p = plan_gemv(d_out, K);
+  if (fused_row_waves() == 16 && tuning().g_target == 0 && p.G > 256) {
+    // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
+    const long T = static_cast<long>(p.nstrips) * K;
+    long G = 256 > p.nstrips ? 256 : p.nstrips;
+    p.chunk = static_cast<int>((T + G - 1) / G);
+    p.G = static_cast<int>((T + p.chunk - 1) / p.chunk);
+    p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;
+  }
   if (p.chunk > kFusedChunkMax) {       // the workgroup's rank list must fit its LDS arrays
     const long T = static_cast<long>(p.nstrips) * K;
     p.chunk = kFusedChunkMax;
@@ -182,7 +205,7 @@ GemvPlan plan_fused(int d_out, int K) {
 }
 
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s) {
-  return bf16 ? launch_nv<BF16>(a, s) : launch_nv<F16>(a, s);
+  return bf16 ? launch_rw<BF16>(a, s) : launch_rw<F16>(a, s);
 }
 
 }  // namespace larosa

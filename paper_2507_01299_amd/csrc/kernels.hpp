@@ -40,6 +40,7 @@ struct Tuning {
   int min_rows = 8;           // minimum row-strips per workgroup
   int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
+  int fused_rw = 8;           // row-waves of the fused kernel: 8 (two workgroups per CU) or 16 (one)
 };
 Tuning& tuning();
 
@@ -62,6 +63,7 @@ struct FusedArgs {
   int32_t* idx_out;           // nullable: receives the kept indices [B, K], ascending
 };
 GemvPlan plan_fused(int d_out, int K);
+int fused_row_waves();
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 
 // Top-K select over stored 16-bit magnitudes, one workgroup per token.

@@ -59,6 +59,12 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 template <typename T>
 __device__ __forceinline__ float round_store(float f) { return T::to_f32(T::from_f32(f)); }
 
+// SiLU(g) = g / (1 + e^-g) with the hardware exp2 and reciprocal (about 1 ulp each in fp32, far
+// below the 16-bit storage step the result is rounded to).
+__device__ __forceinline__ float silu_f32(float g) {
+  return g * __frcp_rn(1.0f + __expf(-g));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -57,6 +57,10 @@ struct TopkLane {
   unsigned r;          // number of keys == T to keep (>= 1)
   unsigned gt_before;  // kept-by-magnitude elements before this lane's first element
   unsigned eq_before;  // threshold ties before this lane's first element
+  unsigned n_gt, n_eq; // this lane's own counts of keys > T and == T
+  // ranks [first, end) of the ascending kept list held by this lane
+  __device__ __forceinline__ unsigned first_rank() const { return gt_before + min(eq_before, r); }
+  __device__ __forceinline__ unsigned end_rank() const { return gt_before + n_gt + min(eq_before + n_eq, r); }
 };
 
 // raw[q] (q < nvalid) are this lane's stored 16-bit values.  Every lane of the NW-wave workgroup
@@ -126,6 +130,8 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   for (int w = 0; w < wave; ++w) prefix += sm.wave_tot[w];
   out.gt_before = prefix & 0xFFFFu;
   out.eq_before = prefix >> 16;
+  out.n_gt = n_gt;
+  out.n_eq = n_eq;
   return out;
 }
 

@@ -32,12 +32,15 @@ def _run_layer(api, case, B, seed, trace=True):
     return xb, out, tr, dl, ws
 
 
-@pytest.fixture(params=[1, 0], ids=["fused", "separate"])
+@pytest.fixture(params=[(1, 8), (1, 16), (0, 8)], ids=["fused8", "fused16", "separate"])
 def fused_mode(api, request):
-    """Run the layer with the Top-K fused into the projection kernels and as separate kernels."""
-    api.set_tuning(3, request.param)
+    """Run the layer with the Top-K fused into the projection kernels (512- and 1024-lane
+    workgroups) and as separate kernels."""
+    api.set_tuning(3, request.param[0])
+    api.set_tuning(4, request.param[1])
     yield request.param
     api.set_tuning(3, 1)
+    api.set_tuning(4, 8)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
