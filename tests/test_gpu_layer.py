@@ -99,3 +99,69 @@ def test_config1_llama2_7b_layer_full_size(api):
     worst = check_layer_trace(case.layer, xb, tr, out)
     print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
     print("free-run index disagreements:", free_run_index_disagreement(case.layer, xb, tr), flush=True)
+
+
+def test_config2_llama3_8b_gqa_bf16_batched_sparsities(api):
+    """LLaMA3-8B-shaped layer (GQA, d_kv = 1024), bf16, decode batch 1 / 4 / 16 with independent
+    per-token index sets, sparsity 25 / 40 / 50 %."""
+    shape = synth.SHAPES["llama3-8b"]
+    print("building llama3-8b case", flush=True)
+    case = cases.build_block_layer(shape, 0.4, seed=synth.seed_for(2, 0), n_cal=4096)
+    L = case.layer
+    dl = device_layer(case)
+    for p, B in ((0.25, 4), (0.40, 16), (0.50, 1)):
+        Ks = (O.kept_count(shape.d, p), O.kept_count(shape.d_q, p), O.kept_count(shape.d, p),
+              O.kept_count(shape.d_ff, p))
+        assert Ks in ((3072, 3072, 3072, 10752), (2457, 2457, 2457, 8601), (2048, 2048, 2048, 7168))
+        L.K1, L.K2, L.K3, L.K4 = Ks
+        dl.c.K1, dl.c.K2, dl.c.K3, dl.c.K4 = Ks
+        print(f"sparsity {p} batch {B}", flush=True)
+        xb, _ = cases.tokens(case, B, synth.seed_for(2, 5) + B)
+        ws = api.Workspace(dl.workspace_bytes(B))
+        x = to_dev(xb, shape.dtype)
+        out = torch.zeros_like(x)
+        tr = dl.trace_buffers(B)
+        api.layer_forward(dl, x, out, ws, tr)
+        torch.cuda.synchronize()
+        worst = check_layer_trace(L, xb, tr, out)
+        print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+        # independent tokens really have different index sets
+        if B > 1:
+            i4 = tr["idx4"].cpu().numpy()
+            assert not np.array_equal(i4[0], i4[1])
+
+
+def test_config3_llama2_70b_layer_on_one_gpu(api):
+    """LLaMA2-70B-shaped single layer, bf16, batch 1, 40 % sparsity, heavy-tailed (Student-t, nu=3)
+    latent activations, PCA rotations (8192 x 8192) from 8192 synthetic calibration tokens."""
+    shape = synth.SHAPES["llama2-70b"]
+    print("building llama2-70b case (PCA at d=8192 on the host)", flush=True)
+    case = cases.build_block_layer(shape, 0.4, seed=synth.seed_for(3, 0), n_cal=8192, latent="t3")
+    assert (case.layer.K1, case.layer.K4) == (4915, 17203)
+    print("running", flush=True)
+    xb, out, tr, dl, ws = _run_layer(api, case, 1, seed=synth.seed_for(3, 5))
+    worst = check_layer_trace(case.layer, xb, tr, out)
+    print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
+def test_config4_folded_stack_llama2_7b_shape(api):
+    """Deployed form at LLaMA2-7B layer shape: rotations folded (no explicit Q), per-layer adapter as
+    a dense 4096 x 4096 mat-vec; a 2-layer slice of the stack, batch 8, every stage of every layer
+    checked.  (The full 32-layer stack differs only in the number of such layers.)"""
+    shape = synth.SHAPES["llama2-7b"]
+    print("building 2 folded llama2-7b layers", flush=True)
+    layers, bits, Qs, Ws, src = cases.build_folded_stack(shape, 2, 0.4, seed=synth.seed_for(4, 0), n_cal=4096)
+    B = 8
+    x0 = O.rotate(src.draw(B, seed=synth.seed_for(4, 5)), Qs[0])
+    cur = to_dev(O.encode16(x0, shape.dtype), shape.dtype)
+    for li, (L, b) in enumerate(zip(layers, bits)):
+        print(f"layer {li}", flush=True)
+        dl = device_layer(cases.LayerCase(shape, b, L, {}, src))
+        ws = api.Workspace(dl.workspace_bytes(B))
+        out = torch.zeros_like(cur)
+        tr = dl.trace_buffers(B)
+        api.layer_forward(dl, cur, out, ws, tr)
+        torch.cuda.synchronize()
+        check_layer_trace(L, to_bits(cur), tr, out)
+        cur = out
+        del dl, ws, tr
