@@ -19,12 +19,39 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool dtype_ok(int t) { return t == LAROSA_F16 || t == LAROSA_BF16; }
 
-size_t gemv_partial_bytes_bound(int B, int d_out_max) {
+size_t gemv_partial_bytes_bound(int B, int d_in_max, int d_out_max) {
   const int sc = 512;
   const long nstrips = (d_out_max + sc - 1) / sc;
   long G = tuning().g_target > 0 ? tuning().g_target : 512;
   if (G < nstrips) G = nstrips;
+  if (B > 1) {   // batched kernels: chunk is capped, so very large products use more workgroups
+    const long by_rows = (nstrips * d_in_max + kBatchChunkMax - 1) / kBatchChunkMax;
+    if (G < by_rows) G = by_rows;
+    B = (B + 31) / 32 * 32;   // token groups are padded
+  }
   return static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * sc * sizeof(float);
+}
+
+size_t batched_partial_bytes(const GemvPlan& p, int B, bool coef_scale) {
+  const int tpg = batched_tokens_per_group(B, coef_scale);
+  const size_t groups = (B + tpg - 1) / tpg;
+  return groups * tpg * p.partial_floats * sizeof(float);
+}
+
+// One launch of the batched kernels (B > 1): C holds the tokens' coefficients over all rows.
+int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
+  const GemvPlan p = plan_batched(a.d_in, a.d_out);
+  const int tpg = batched_tokens_per_group(a.B, a.coef_scale != nullptr);
+  const size_t groups = (a.B + tpg - 1) / tpg;
+  if (groups * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  const size_t need = kCounterBytes + batched_partial_bytes(p, a.B, a.coef_scale != nullptr);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  a.chunk = p.chunk;
+  a.G = p.G;
+  a.nstrips = p.nstrips;
+  a.counters = static_cast<unsigned*>(ws);
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  return launch_batched(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
 struct Carver {
@@ -95,7 +122,10 @@ int larosa_version(void) { return 100; }
 
 size_t larosa_workspace_bytes(int B, int d_in_max, int d_out_max, int K_max) {
   if (B < 1 || d_in_max < 1 || d_out_max < 1 || K_max < 1) return 0;
-  return round_up(kCounterBytes + gemv_partial_bytes_bound(B, d_out_max), 256);
+  // counters | partial strips | (B > 1) masked coefficient matrix of larosa_sparse_gemv
+  size_t n = round_up(kCounterBytes + gemv_partial_bytes_bound(B, d_in_max, d_out_max), 256);
+  if (B > 1) n += round_up(static_cast<size_t>(B) * d_in_max * 2, 256);
+  return n;
 }
 
 int larosa_workspace_init(void* ws, size_t ws_bytes, void* stream) {
@@ -111,6 +141,14 @@ int larosa_dense_gemv(const void* Wp, const void* x, void* y, int B, int d_in, i
   if (!Wp || !x || !y || !dtype_ok(t)) return LAROSA_EINVAL;
   if (!aligned(Wp, 16) || !aligned(x, 16) || !aligned(y, 16)) return LAROSA_EINVAL;
   if (int rc = check_gemv_shapes(B, d_in, d_out, d_in)) return rc;
+  if (B > 1) {
+    BatchArgs ba{};
+    ba.W = static_cast<const uint16_t*>(Wp);
+    ba.C = static_cast<const uint16_t*>(x);
+    ba.y = static_cast<uint16_t*>(y);
+    ba.d_in = d_in; ba.d_out = d_out; ba.B = B;
+    return run_batched(ba, t == LAROSA_BF16, ws, ws_bytes, static_cast<hipStream_t>(stream));
+  }
   GemvArgs a{};
   a.W = static_cast<const uint16_t*>(Wp);
   a.h = static_cast<const uint16_t*>(x);
@@ -132,7 +170,7 @@ int larosa_topk(const void* h, int B, int d, int K, int32_t* idx, void* vals, la
   if (!aligned(h, 16) || !aligned(idx, 4) || (vals && !aligned(vals, 2))) return LAROSA_EINVAL;
   if (B < 1 || d < 8 || d % 8 || K < 1 || K > d) return LAROSA_EINVAL;
   if (d > kMaxTopkD || B > 65535) return LAROSA_EUNSUPPORTED;
-  return launch_topk(static_cast<const uint16_t*>(h), B, d, K, idx, static_cast<uint16_t*>(vals),
+  return launch_topk(static_cast<const uint16_t*>(h), B, d, K, idx, static_cast<uint16_t*>(vals), nullptr,
                      static_cast<hipStream_t>(stream)) == hipSuccess
              ? LAROSA_OK
              : LAROSA_EHIP;
@@ -143,6 +181,22 @@ int larosa_sparse_gemv(const void* Wp, const void* h, const int32_t* idx, void* 
   if (!Wp || !h || !idx || !y || !dtype_ok(t)) return LAROSA_EINVAL;
   if (!aligned(Wp, 16) || !aligned(h, 16) || !aligned(y, 16) || !aligned(idx, 4)) return LAROSA_EINVAL;
   if (int rc = check_gemv_shapes(B, d_in, d_out, K)) return rc;
+  if (B > 1) {
+    // masked coefficient matrix in the tail of the workspace, then one pass over the weight
+    const GemvPlan p = plan_batched(d_in, d_out);
+    const size_t head = round_up(kCounterBytes + batched_partial_bytes(p, B, false), 256);
+    const size_t cbytes = static_cast<size_t>(B) * d_in * 2;
+    if (!ws || !aligned(ws, 256) || ws_bytes < head + cbytes) return LAROSA_EWORKSPACE;
+    uint16_t* C = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + head);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_batch_prep(static_cast<const uint16_t*>(h), idx, C, B, d_in, K, st) != hipSuccess) return LAROSA_EHIP;
+    BatchArgs ba{};
+    ba.W = static_cast<const uint16_t*>(Wp);
+    ba.C = C;
+    ba.y = static_cast<uint16_t*>(y);
+    ba.d_in = d_in; ba.d_out = d_out; ba.B = B;
+    return run_batched(ba, t == LAROSA_BF16, ws, head, st);
+  }
   GemvArgs a{};
   a.W = static_cast<const uint16_t*>(Wp);
   a.h = static_cast<const uint16_t*>(h);
@@ -186,6 +240,15 @@ static size_t layer_gemv_ws(const larosa_layer* L, int B) {
     const size_t need = round_up(kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float), 256);
     if (need > s) s = need;
   }
+  if (B > 1) {
+    const bool cs = L->rms_attn || L->rms_mlp;
+    const GemvPlan bp[] = {plan_batched(L->d, L->d), plan_batched(L->d, L->d_q + 2 * L->d_kv),
+                           plan_batched(L->d_q, L->d), plan_batched(L->d, 2 * L->d_ff), plan_batched(L->d_ff, L->d)};
+    for (const GemvPlan& p : bp) {
+      const size_t need = round_up(kCounterBytes + batched_partial_bytes(p, B, cs), 256);
+      if (need > s) s = need;
+    }
+  }
   return s;
 }
 
@@ -199,6 +262,7 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
   for (size_t w : widths) s += round_up(Bz * w * E, 256) + 256;
   const int Ks[] = {L->K1, L->K2, L->K3, L->K4};
   for (int k : Ks) s += round_up(Bz * k * sizeof(int32_t), 256) + 256;
+  if (B > 1) s += round_up(Bz * max3(L->d, L->d_q, L->d_ff) * E, 256) + 256;   // masked activations
   return s;
 }
 
@@ -238,6 +302,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   int32_t* idx2 = bufidx(T.idx2, L->K2);
   int32_t* idx3 = bufidx(T.idx3, L->K3);
   int32_t* idx4 = bufidx(T.idx4, L->K4);
+  uint16_t* masked = B > 1 ? static_cast<uint16_t*>(cv.take(Bz * max3(d, d_q, d_ff) * 2)) : nullptr;
   if (!cv.ok) return LAROSA_EWORKSPACE;
   const uint16_t* x = static_cast<const uint16_t*>(x_in);
 
@@ -253,6 +318,18 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
 
   // block input: pre-norm, rotation, one rounding
   auto block_input = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* dst) -> int {
+    if (Q && B > 1) {
+      BatchArgs a{};
+      a.W = static_cast<const uint16_t*>(Q);
+      a.C = src; a.y = dst;
+      a.d_in = d; a.d_out = d; a.B = B;
+      if (norm) {
+        a.rms_src = src;
+        a.rms_eps = L->rms_eps;
+        a.coef_scale = static_cast<const uint16_t*>(scale);
+      }
+      return run_batched(a, bf, ws, gws, st);
+    }
     if (Q) {
       GemvArgs a{};
       a.W = static_cast<const uint16_t*>(Q);
@@ -281,7 +358,31 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     return run_gemv(a, bf, ws, gws, st);
   };
 
-  if (tuning().fused) {
+  if (B > 1) {
+    // Batched decode: per-token Top-K writes each token's activations with the dropped channels
+    // zeroed, and one pass over all weight rows serves every token (the union of the index sets).
+    auto project = [&](const void* W, int d_in, int d_out, uint16_t* y, const uint16_t* residual,
+                       uint16_t* y_pre) -> int {
+      BatchArgs a{};
+      a.W = static_cast<const uint16_t*>(W);
+      a.C = masked; a.y = y;
+      a.d_in = d_in; a.d_out = d_out; a.B = B;
+      a.residual = residual; a.y_pre = y_pre;
+      return run_batched(a, bf, ws, gws, st);
+    };
+    LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
+    LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, masked, st));
+    LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr));
+    LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
+    LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, masked, st));
+    LAROSA_TRY(project(L->Wo, d_q, d, x1, x, o));
+    LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
+    LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, masked, st));
+    LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr));
+    LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
+    LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, masked, st));
+    LAROSA_TRY(project(L->Wdown, d_ff, d, x2, x1, down));
+  } else if (tuning().fused) {
     // Top-K fused into the projections: 4 projection kernels (+ one rotation each when Q is given)
     auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
                      const uint16_t* residual, uint16_t* y_pre, uint16_t* h_out, int32_t* idx_out,
@@ -316,21 +417,27 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
   LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
-  LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, st));
+  LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wqkv, h1, idx1, qkv, d, d_qkv, L->K1, nullptr, nullptr));
   LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
-  LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, st));
+  LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, x, o));
   // MLP block: h3 -> gate|up -> h4 -> down -> + residual
   LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
-  LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, st));
+  LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wgu, h3, idx3, gu, d, 2 * d_ff, L->K3, nullptr, nullptr));
   LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
-  LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, st));
+  LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
   }
   // residual adapter
-  if (L->adapter) {
+  if (L->adapter && B > 1) {
+    BatchArgs a{};
+    a.W = static_cast<const uint16_t*>(L->adapter);
+    a.C = x2; a.y = static_cast<uint16_t*>(x_out);
+    a.d_in = d; a.d_out = d; a.B = B;
+    LAROSA_TRY(run_batched(a, bf, ws, gws, st));
+  } else if (L->adapter) {
     GemvArgs a{};
     a.W = static_cast<const uint16_t*>(L->adapter);
     a.h = x2; a.y = static_cast<uint16_t*>(x_out);

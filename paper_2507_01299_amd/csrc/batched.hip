@@ -1,0 +1,542 @@
+// Batched variant of the column-sparse projection for gfx950: B tokens with independent per-token
+// index sets.  The union of the tokens' kept rows is what has to be read; at the sparsities of
+// interest it is nearly every row once B >= 4 (1 - p^B of them), so the weight is streamed once
+// over all rows and each token's dropped channels simply carry a zero coefficient:
+//     y[b,:] = sum_j C[b,j] * W[j,:],   C[b,j] = h[b,j] if j in idx_b else 0.
+// The same kernels serve the batched rotation / adapter / dense baseline (C = x).
+//
+//   * up to 4 tokens: plain fp32 FMAs, one 16-byte row piece per lane feeds every token;
+//   * 5..32 tokens: the tile really is a dense contraction, so it goes to the matrix cores
+//     (v_mfma_f32_16x16x16 f16/bf16): M = 16 output columns, N = 16 tokens, K = 16 rows.
+//     A lane loads 8 consecutive columns of 4 rows (16 lanes x 16 bytes = 256 contiguous bytes per
+//     row), and a byte permute regroups those registers into the K-runs the instruction wants;
+//     no LDS staging of the weight is needed.
+// Work split, cross-workgroup hand-off and epilogue follow the single-token kernel
+// (gemv_core.hpp), with one arrival per workgroup for all its tokens.
+#include "gemv_core.hpp"
+
+namespace larosa {
+
+namespace {
+
+constexpr int kBRW = 8;                 // row-waves of the FMA kernel
+constexpr int kBThreads = 512;
+
+// ------------------------------------------------------------------------------------------------
+// masked coefficient matrix from (h, idx): C[b,:] = 0, then C[b, idx[b,t]] = h[b, idx[b,t]]
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void batch_prep_kernel(const uint16_t* __restrict__ h, const int32_t* __restrict__ idx,
+                                                         uint16_t* __restrict__ C, int d_in, int K) {
+  const int b = blockIdx.x;
+  uint16_t* cb = C + static_cast<size_t>(b) * d_in;
+  for (int i = threadIdx.x * 8; i < d_in; i += 512 * 8) *reinterpret_cast<uint4*>(cb + i) = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();   // this workgroup wrote the whole row itself
+  const uint16_t* hb = h + static_cast<size_t>(b) * d_in;
+  const int32_t* ib = idx + static_cast<size_t>(b) * K;
+  for (int t = threadIdx.x; t < K; t += 512) {
+    const int j = ib[t];
+    cb[j] = hb[j];
+  }
+}
+
+struct Geometry {
+  int s, t0, t1;          // strip and row range of a segment
+  int g_first, g_last;    // workgroups that contribute to the strip
+};
+
+__device__ __forceinline__ Geometry strip_geometry(int s, int t0, int t1, int K, int chunk) {
+  Geometry q{s, t0, t1, (s * K) / chunk, ((s + 1) * K - 1) / chunk};
+  return q;
+}
+
+// per-token pre-norm factor 1/sqrt(mean(x^2)+eps): wave w handles tokens w, w+NW, ...
+template <typename T, int NW>
+__device__ __forceinline__ void token_scales(const BatchArgs& a, int b0, int ntok, float* scale_s, int lane, int wave) {
+  for (int bb = wave; bb < ntok; bb += NW) {
+    float sc = 1.f;
+    const int tok = b0 + bb;
+    if (a.rms_src && tok < a.B) {
+      const uint16_t* xs = a.rms_src + static_cast<size_t>(tok) * a.d_in;
+      float ss = 0.f;
+      for (int i = lane * 8; i < a.d_in; i += 64 * 8) {
+        float w[8];
+        unpack8<T>(*reinterpret_cast<const uint4*>(xs + i), w);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ss = fmaf(w[k], w[k], ss);
+      }
+      ss = wave_sum(ss);
+      sc = 1.0f / sqrtf(ss / static_cast<float>(a.d_in) + a.rms_eps);
+    }
+    if (lane == 0) scale_s[bb] = sc;
+  }
+}
+
+// epilogue for 8 consecutive columns of one token
+template <typename T>
+__device__ __forceinline__ void store_out8(const BatchArgs& a, int tok, int col, float (&v)[8], float scale) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k) v[k] *= scale;
+  const size_t off = static_cast<size_t>(tok) * a.d_out + col;
+  if (a.residual) {
+    if (a.y_pre) *reinterpret_cast<uint4*>(a.y_pre + off) = pack8<T>(v);
+    float r[8];
+    unpack8<T>(*reinterpret_cast<const uint4*>(a.residual + off), r);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
+  }
+  *reinterpret_cast<uint4*>(a.y + off) = pack8<T>(v);
+}
+
+// ------------------------------------------------------------------------------------------------
+// FMA kernel, NB <= 4 tokens per workgroup
+// ------------------------------------------------------------------------------------------------
+template <typename T, int NB>
+__global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
+  __shared__ float coef[NB][kBatchChunkMax];
+  __shared__ float red[kBRW - 1][8][64];
+  __shared__ float scale_s[NB];
+  __shared__ int s_last;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = blockIdx.x;
+  const int grp = blockIdx.y;
+  const int b0 = grp * NB;
+  const int K = a.d_in;
+  const int chunk = a.chunk;
+
+  int f0 = g * chunk;
+  const int f1 = min(f0 + chunk, a.nstrips * K);
+  int s = f0 / K;
+  int t0 = f0 - s * K;
+  int seg_no = 0;
+  while (f0 < f1) {
+    const int t1 = min(K, t0 + (f1 - f0));
+    const int n = t1 - t0;
+    const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
+    const int col = s * kStripCols + lane * 8;
+    const bool colv = col < a.d_out;
+
+    // this segment's coefficients, as floats, for the NB tokens
+    for (int e = tid; e < NB * n; e += kBThreads) {
+      const int bb = e / n;
+      const int t = e - bb * n;
+      const int tok = b0 + bb;
+      float c = 0.f;
+      if (tok < a.B) {
+        c = T::to_f32(a.C[static_cast<size_t>(tok) * K + t0 + t]);
+        if (a.coef_scale) c *= T::to_f32(a.coef_scale[t0 + t]);
+      }
+      coef[bb][t] = c;
+    }
+    __syncthreads();
+
+    float acc[NB][8];
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[bb][k] = 0.f;
+    const int per = (n + kBRW - 1) / kBRW;
+    const int ra = t0 + rw * per;
+    const int re = min(t1, ra + per);
+    if (colv) {
+      const uint16_t* wcol = a.W + col;
+      for (int t = ra; t < re; t += kUnroll) {
+        uint4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = load_stream16(wcol + static_cast<size_t>(min(t + u, re - 1)) * a.d_out);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          float w[8];
+          unpack8<T>(v[u], w);
+          const bool ok = t + u < re;
+          const int ti = min(t + u, re - 1) - t0;
+#pragma unroll
+          for (int bb = 0; bb < NB; ++bb) {
+            const float c = ok ? coef[bb][ti] : 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[bb][k] = fmaf(c, w[k], acc[bb][k]);
+          }
+        }
+      }
+    }
+
+    // row-waves -> one strip partial per token
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb) {
+      if (rw > 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) red[rw - 1][k][lane] = acc[bb][k];
+      }
+      __syncthreads();
+      if (rw == 0) {
+        for (int r = 0; r < kBRW - 1; ++r) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][k][lane];
+        }
+      }
+      __syncthreads();
+    }
+
+    const int n_s = ge.g_last - ge.g_first + 1;
+    bool last = (n_s == 1);
+    if (n_s > 1) {
+      const size_t slot_floats = static_cast<size_t>(NB) * kStripCols;
+      unsigned long long* slot = reinterpret_cast<unsigned long long*>(
+          a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
+      unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
+      if (rw == 0) {
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(acc[bb][2 * k])) |
+                                         (static_cast<unsigned long long>(__float_as_uint(acc[bb][2 * k + 1])) << 32);
+            __hip_atomic_store(slot + bb * 256 + k * 64 + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (tid == 0) {
+        const unsigned old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (old == static_cast<unsigned>(n_s - 1)) ? 1 : 0;
+      }
+      __syncthreads();
+      last = (s_last != 0);
+      if (last) {
+        if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc[bb][k] = 0.f;
+          for (int gg = ge.g_first + rw; gg <= ge.g_last; gg += 4 * kBRW) {
+            unsigned long long v[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int g2 = min(gg + q * kBRW, ge.g_last);
+              const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
+              const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
+                  a.partial + ((static_cast<size_t>(grp) * a.G + g2) * 2 + sgn) * slot_floats);
+#pragma unroll
+              for (int k = 0; k < 4; ++k)
+                v[q][k] = __hip_atomic_load(p + bb * 256 + k * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              if (gg + q * kBRW <= ge.g_last) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                  acc[bb][2 * k] += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
+                  acc[bb][2 * k + 1] += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
+                }
+              }
+            }
+          }
+          if (rw > 0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) red[rw - 1][k][lane] = acc[bb][k];
+          }
+          __syncthreads();
+          if (rw == 0) {
+            for (int r = 0; r < kBRW - 1; ++r) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][k][lane];
+            }
+          }
+          __syncthreads();
+        }
+      }
+    }
+    if (last) {   // uniform over the workgroup
+      token_scales<T, kBRW>(a, b0, NB, scale_s, lane, rw);
+      __syncthreads();
+      if (rw == 0 && colv) {
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+          if (b0 + bb < a.B) store_out8<T>(a, b0 + bb, col, acc[bb], scale_s[bb]);
+      }
+    }
+    __syncthreads();
+    f0 += t1 - t0;
+    s += 1;
+    t0 = 0;
+    seg_no += 1;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// matrix-core kernel, NTB blocks of 16 tokens per workgroup
+// ------------------------------------------------------------------------------------------------
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ float4_t mfma16(uint2 a, uint2 b, float4_t c);
+template <>
+__device__ __forceinline__ float4_t mfma16<F16>(uint2 a, uint2 b, float4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ float4_t mfma16<BF16>(uint2 a, uint2 b, float4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4_t, a), __builtin_bit_cast(short4_t, b), c, 0,
+                                                   0, 0);
+}
+
+constexpr int kTileStride = 516;   // floats per token row of the LDS strip tile (16-byte aligned, off the bank period)
+
+template <typename T, int NTB>
+__global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
+  constexpr int RWM = 2;   // row-waves; 4 column-waves of 128 columns each
+  __shared__ float tile[16][kTileStride];
+  __shared__ float scale_s[NTB * 16];
+  __shared__ int s_last;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cwm = wave & 3;
+  const int rwm = wave >> 2;
+  const int kgrp = lane >> 4;    // K-run of 4 rows inside a 16-row tile
+  const int m = lane & 15;       // column group (A operand) / token (B operand)
+  const int g = blockIdx.x;
+  const int grp = blockIdx.y;
+  const int b0 = grp * NTB * 16;
+  const int K = a.d_in;
+  const int chunk = a.chunk;
+
+  int f0 = g * chunk;
+  const int f1 = min(f0 + chunk, a.nstrips * K);
+  int s = f0 / K;
+  int t0 = f0 - s * K;
+  int seg_no = 0;
+  while (f0 < f1) {
+    const int t1 = min(K, t0 + (f1 - f0));
+    const int n = t1 - t0;
+    const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
+    const int colbase = s * kStripCols + cwm * 128 + 8 * m;   // this lane's 8 columns (A operand)
+    const bool colv = colbase < a.d_out;
+
+    float4_t acc[NTB][8];
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[tb][i] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int ntiles = (n + 15) / 16;
+    const int per = (ntiles + RWM - 1) / RWM;
+    const int tl0 = rwm * per;
+    const int tl1 = min(ntiles, tl0 + per);
+    for (int tl = tl0; tl < tl1; ++tl) {
+      const int j0 = t0 + tl * 16 + 4 * kgrp;        // first of this lane's 4 rows; t0 % 8 == 0, so j0 % 4 == 0
+      uint4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = min(j0 + q, t1 - 1);
+        v[q] = colv ? load_stream16(a.W + static_cast<size_t>(r) * a.d_out + colbase) : make_uint4(0u, 0u, 0u, 0u);
+      }
+      // B operand: 4 consecutive rows of token (b0 + tb*16 + m); rows at or past t1 belong to
+      // another workgroup (or do not exist) and must contribute nothing
+      uint2 bf[NTB];
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tok = b0 + tb * 16 + m;
+        uint2 c = make_uint2(0u, 0u);
+        if (tok < a.B && j0 < t1) c = *reinterpret_cast<const uint2*>(a.C + static_cast<size_t>(tok) * K + j0);
+        if (j0 + 1 >= t1) c.x &= 0x0000FFFFu;
+        if (j0 + 2 >= t1) c.y = 0u;
+        if (j0 + 3 >= t1) c.y &= 0x0000FFFFu;
+        if (j0 >= t1) c.x = 0u;
+        bf[tb] = c;
+      }
+      // A operand for column offset i: element i of each of the 4 row registers
+      const uint32_t* vw0 = reinterpret_cast<const uint32_t*>(&v[0]);
+      const uint32_t* vw1 = reinterpret_cast<const uint32_t*>(&v[1]);
+      const uint32_t* vw2 = reinterpret_cast<const uint32_t*>(&v[2]);
+      const uint32_t* vw3 = reinterpret_cast<const uint32_t*>(&v[3]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        uint2 af;
+        af.x = __builtin_amdgcn_perm(vw1[i >> 1], vw0[i >> 1], sel);
+        af.y = __builtin_amdgcn_perm(vw3[i >> 1], vw2[i >> 1], sel);
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) acc[tb][i] = mfma16<T>(af, bf[tb], acc[tb][i]);
+      }
+    }
+
+    const int n_s = ge.g_last - ge.g_first + 1;
+    const size_t slot_floats = static_cast<size_t>(NTB) * 16 * kStripCols;
+    unsigned long long* slot = reinterpret_cast<unsigned long long*>(
+        a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
+    unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
+
+    // Per token block: sum the two row-waves into the LDS tile [token][512 columns]; D element e of
+    // MFMA i in lane (kgrp, m) is column cwm*128 + 32*kgrp + 8*e + i of token m.
+    auto tile_pass = [&](int tb, bool to_global) {
+#pragma unroll
+      for (int r = 0; r < RWM; ++r) {
+        if (rwm == r) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float* p = &tile[m][cwm * 128 + 32 * kgrp + 8 * e + i];
+              *p = (r == 0) ? acc[tb][i][e] : *p + acc[tb][i][e];
+            }
+        }
+        __syncthreads();
+      }
+      if (to_global) {
+        // 16 x 512 floats = 4096 float pairs, 8 per thread, each store instruction 512 contiguous bytes
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int q = tid + k * kBThreads;          // pair index: token = q / 256, pair in row = q % 256
+          const float2 pr = *reinterpret_cast<const float2*>(&tile[q >> 8][(q & 255) * 2]);
+          const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(pr.x)) |
+                                       (static_cast<unsigned long long>(__float_as_uint(pr.y)) << 32);
+          __hip_atomic_store(slot + static_cast<size_t>(tb) * 4096 + q, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+      }
+    };
+    // epilogue of one token block from the LDS tile: 16 tokens x 64 column groups of 8
+    auto tile_out = [&](int tb) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int gid = tid + k * kBThreads;
+        const int tok = b0 + tb * 16 + (gid >> 6);
+        const int col = s * kStripCols + (gid & 63) * 8;
+        if (tok < a.B && col < a.d_out) {
+          float v[8];
+          const float* p = &tile[gid >> 6][(gid & 63) * 8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = p[e];
+          store_out8<T>(a, tok, col, v, scale_s[tb * 16 + (gid >> 6)]);
+        }
+      }
+      __syncthreads();
+    };
+
+    if (n_s == 1) {
+      token_scales<T, 8>(a, b0, NTB * 16, scale_s, lane, wave);
+      __syncthreads();
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        tile_pass(tb, false);
+        tile_out(tb);
+      }
+    } else {
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) tile_pass(tb, true);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (tid == 0) {
+        const unsigned old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (old == static_cast<unsigned>(n_s - 1)) ? 1 : 0;
+      }
+      __syncthreads();
+      if (s_last != 0) {   // uniform over the workgroup
+        if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        token_scales<T, 8>(a, b0, NTB * 16, scale_s, lane, wave);
+        for (int tb = 0; tb < NTB; ++tb) {
+          // each thread owns 8 float pairs of the block and adds the partials in workgroup order
+          float2 sum[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) sum[k] = make_float2(0.f, 0.f);
+          for (int gg = ge.g_first; gg <= ge.g_last; gg += 2) {
+            unsigned long long v[2][8];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              const int g2 = min(gg + q, ge.g_last);
+              const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
+              const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
+                  a.partial + ((static_cast<size_t>(grp) * a.G + g2) * 2 + sgn) * slot_floats);
+#pragma unroll
+              for (int k = 0; k < 8; ++k)
+                v[q][k] = __hip_atomic_load(p + static_cast<size_t>(tb) * 4096 + tid + k * kBThreads, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              if (gg + q <= ge.g_last) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                  sum[k].x += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
+                  sum[k].y += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
+                }
+              }
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const int q = tid + k * kBThreads;
+            *reinterpret_cast<float2*>(&tile[q >> 8][(q & 255) * 2]) = sum[k];
+          }
+          __syncthreads();
+          tile_out(tb);
+        }
+      }
+    }
+    __syncthreads();
+    f0 += t1 - t0;
+    s += 1;
+    t0 = 0;
+    seg_no += 1;
+  }
+}
+
+template <typename T>
+hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
+  const dim3 block(kBThreads);
+  if (a.B <= 4 || a.coef_scale) {
+    // (a per-channel coefficient scale is applied in fp32, which only the FMA kernel does)
+    if (a.B <= 2) {
+      hipLaunchKernelGGL((skinny_fma_kernel<T, 2>), dim3(a.G, (a.B + 1) / 2), block, 0, st, a);
+    } else {
+      hipLaunchKernelGGL((skinny_fma_kernel<T, 4>), dim3(a.G, (a.B + 3) / 4), block, 0, st, a);
+    }
+  } else if (a.B <= 16) {
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G, 1), block, 0, st, a);
+  } else {
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 2>), dim3(a.G, (a.B + 31) / 32), block, 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int batched_tokens_per_group(int B, bool coef_scale) {
+  if (B <= 2) return 2;
+  if (B <= 4 || coef_scale) return 4;
+  return B <= 16 ? 16 : 32;
+}
+
+GemvPlan plan_batched(int d_in, int d_out) {
+  GemvPlan p;
+  p.strip_cols = kStripCols;
+  p.nstrips = (d_out + kStripCols - 1) / kStripCols;
+  const long T = static_cast<long>(p.nstrips) * d_in;
+  long G = tuning().g_target > 0 ? tuning().g_target : 256;     // one workgroup per compute unit
+  if (G < p.nstrips) G = p.nstrips;
+  long chunk = (T + G - 1) / G;
+  chunk = (chunk + 15) / 16 * 16;                                // whole 16-row tiles; keeps row starts 8-aligned
+  if (chunk > kBatchChunkMax) chunk = kBatchChunkMax;
+  if (chunk > d_in) chunk = d_in;                                // a workgroup touches at most two strips
+  p.chunk = static_cast<int>(chunk);
+  p.G = static_cast<int>((T + chunk - 1) / chunk);
+  p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;  // per token
+  return p;
+}
+
+hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C, int B, int d_in, int K, hipStream_t s) {
+  hipLaunchKernelGGL(batch_prep_kernel, dim3(B), dim3(512), 0, s, h, idx, C, d_in, K);
+  return hipGetLastError();
+}
+
+hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s) {
+  return bf16 ? launch_batched_t<BF16>(a, s) : launch_batched_t<F16>(a, s);
+}
+
+}  // namespace larosa

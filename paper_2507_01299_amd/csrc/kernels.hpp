@@ -66,8 +66,33 @@ GemvPlan plan_fused(int d_out, int K);
 int fused_row_waves();
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 
-// Top-K select over stored 16-bit magnitudes, one workgroup per token.
-hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, hipStream_t s);
+// Batched variant: y[b,:] = epilogue( sum_j C[b,j] * W[j,:] ) over ALL rows j, where C holds each
+// token's activations with dropped channels set to zero (or the plain input for a dense product).
+struct BatchArgs {
+  const uint16_t* W;          // [d_in, d_out] input-channel-major
+  const uint16_t* C;          // [B, d_in] coefficients
+  uint16_t* y;                // [B, d_out]
+  int d_in, d_out, B;
+  int chunk, G, nstrips;      // work split over (strip, row) pairs, rows = all d_in
+  float* partial;             // [groups][G][2][tokens per group][512] fp32
+  unsigned* counters;         // [groups][nstrips] arrival counters
+  const uint16_t* coef_scale; // as in GemvArgs
+  const uint16_t* rms_src;
+  float rms_eps;
+  const uint16_t* residual;
+  uint16_t* y_pre;
+};
+constexpr int kBatchChunkMax = 1024;   // rows per workgroup segment (LDS coefficient staging)
+GemvPlan plan_batched(int d_in, int d_out);
+int batched_tokens_per_group(int B, bool coef_scale);
+hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s);
+// C[b,:] = 0 except C[b, idx[b,t]] = h[b, idx[b,t]]
+hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C, int B, int d_in, int K, hipStream_t s);
+
+// Top-K select over stored 16-bit magnitudes, one workgroup per token.  masked (nullable)
+// receives h with the dropped channels set to zero.
+hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
+                       hipStream_t s);
 
 // h2[b,i] = v-part of qkv for the GQA group of query head i/head_dim (context-length-1 attention).
 hipError_t launch_gqa_expand(const uint16_t* qkv, uint16_t* h2, int B, int d_q, int d_kv, int head_dim,

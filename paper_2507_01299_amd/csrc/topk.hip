@@ -13,7 +13,8 @@ constexpr int kTopkWaves = kTopkThreads / 64;
 template <int E>   // elements per lane, multiple of 4
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __restrict__ h, int d, int K,
                                                             int32_t* __restrict__ idx,
-                                                            uint16_t* __restrict__ vals) {
+                                                            uint16_t* __restrict__ vals,
+                                                            uint16_t* __restrict__ masked) {
   __shared__ TopkShared<kTopkWaves> sm;
   const int b = blockIdx.x;
   const uint16_t* hb = h + static_cast<size_t>(b) * d;
@@ -35,29 +36,47 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
 
   int32_t* idxb = idx + static_cast<size_t>(b) * K;
   uint16_t* valb = vals ? vals + static_cast<size_t>(b) * K : nullptr;
+  uint16_t mk[E];
+#pragma unroll
+  for (int q = 0; q < E; ++q) mk[q] = 0;
   for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned pos) {
     if (pos < static_cast<unsigned>(K)) {   // always true; keeps a stray position inside the row
       idxb[pos] = base + q;
       if (valb) valb[pos] = raw[q];
+      mk[q] = raw[q];
     }
   });
+  if (masked) {
+    uint16_t* mb = masked + static_cast<size_t>(b) * d;
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q) {
+      const int i = base + q * 4;
+      if (i < d) {
+        uint2 v;
+        v.x = mk[q * 4 + 0] | (static_cast<uint32_t>(mk[q * 4 + 1]) << 16);
+        v.y = mk[q * 4 + 2] | (static_cast<uint32_t>(mk[q * 4 + 3]) << 16);
+        *reinterpret_cast<uint2*>(mb + i) = v;
+      }
+    }
+  }
 }
 
 }  // namespace
 
-hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, hipStream_t s) {
+hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
+                       hipStream_t s) {
   dim3 grid(B), block(kTopkThreads);
   const int e = (d + kTopkThreads - 1) / kTopkThreads;
   if (e <= 4)
-    hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, s, h, d, K, idx, vals);
+    hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, s, h, d, K, idx, vals, masked);
   else if (e <= 8)
-    hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, s, h, d, K, idx, vals);
+    hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, s, h, d, K, idx, vals, masked);
   else if (e <= 16)
-    hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, s, h, d, K, idx, vals);
+    hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, s, h, d, K, idx, vals, masked);
   else if (e <= 24)
-    hipLaunchKernelGGL(topk_kernel<24>, grid, block, 0, s, h, d, K, idx, vals);
+    hipLaunchKernelGGL(topk_kernel<24>, grid, block, 0, s, h, d, K, idx, vals, masked);
   else if (e <= 32)
-    hipLaunchKernelGGL(topk_kernel<32>, grid, block, 0, s, h, d, K, idx, vals);
+    hipLaunchKernelGGL(topk_kernel<32>, grid, block, 0, s, h, d, K, idx, vals, masked);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -166,3 +166,48 @@ def test_sparse_gemv_every_launch_shape(api, variant, g_target, min_rows):
     got = O.decode16(to_bits(y), dtype)
     for b in range(2):
         assert rel_l2(got[b], O.round16(O.sparse_project_gather(h[b], idx[b], W), dtype)) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B", [2, 4, 5, 16, 17, 33])
+def test_batched_sparse_gemv_per_token_index_sets(api, dtype, B):
+    """Batched variant: independent index sets per token; 2-4 tokens take the FMA kernel, 5-32 the
+    matrix-core kernel, more than 32 several token groups.  Row count not a multiple of the 16-row
+    tile, output width with a ragged last strip."""
+    d_in, d_out, K = 1032, 1544, 413
+    print(f"batched sparse_gemv dtype={dtype} B={B}", flush=True)
+    rng = np.random.default_rng(1000 + B)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, seed=3), dtype)
+    hb, h = _heavy_vector(rng, B, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    ws = api.workspace(B, d_in, d_out, K)
+    y = torch.full((B, d_out), 7.0, dtype=api.torch_dtype(dtype), device="cuda:0")
+    api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+    torch.cuda.synchronize()
+    W = O.decode16(wb, dtype)
+    got = O.decode16(to_bits(y), dtype)
+    for b in range(B):
+        want = O.round16(O.sparse_project_gather(h[b], idx[b], W), dtype)
+        assert rel_l2(got[b], want) <= REL_L2_TOL, b
+    # a second call on the same workspace gives the same bits (counters were left at zero)
+    y2 = torch.zeros_like(y)
+    api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y2, dtype, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(y), to_bits(y2))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d", [(2, 520), (8, 2048), (16, 4096), (32, 1096)])
+def test_batched_rotate_matches_oracle(api, dtype, B, d):
+    print(f"batched rotate dtype={dtype} B={B} d={d}", flush=True)
+    rng = np.random.default_rng(200 + d + B)
+    qb = O.encode16(synth.planted_basis(d, seed=d + 1), dtype)
+    xb, x = _heavy_vector(rng, B, d, dtype)
+    ws = api.workspace(B, d, d, d)
+    h = torch.zeros(B, d, dtype=api.torch_dtype(dtype), device="cuda:0")
+    api.rotate(to_dev(xb, dtype), to_dev(qb, dtype), h, dtype, ws)
+    torch.cuda.synchronize()
+    want = O.round16(O.rotate(x, O.decode16(qb, dtype)), dtype)
+    got = O.decode16(to_bits(h), dtype)
+    for b in range(B):
+        assert rel_l2(got[b], want[b]) <= REL_L2_TOL, b
