@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script scaled by a 1 GiB copy (profiles/gemv_rows_llama2_7b_layer_b1_s40_hbm_traffic.txt).
+# Keyed by (config, batch, sparsity); other workloads have not been counted.
+MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4): 63.2e6}
+
 CONFIGS = {
     1: dict(shape="llama2-7b", workload="LLaMA2-7B-shaped decoder layer, fp16, batch 1, 40% sparsity, "
                                         "explicit Q_attn/Q_mlp from PCA of 4096 synthetic calibration tokens",
@@ -56,6 +61,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--detail", default=None, help="also write the full report to this JSON file")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy kernel) so that hardware counters "
+                         "read under rocprofv3 can be scaled by a transfer of known size")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="larosa_set_tuning(KEY, VALUE) before anything is sized (experiments)")
     args = ap.parse_args()
@@ -113,6 +121,14 @@ def main():
     ws = api.Workspace(layers[0].workspace_bytes(B))
     out = torch.zeros_like(x)
     trace = layers[0].trace_buffers(B)
+
+    if args.copy_calibration:
+        src_c = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst_c = torch.empty_like(src_c)
+        for _ in range(3):
+            dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c
 
     # ---- eager timing: exactly `steps` steps, host launches one C-ABI call per step
     for i in range(args.warmup):
@@ -182,7 +198,32 @@ def main():
 
     reps = max(1, args.steps // nsets)
     sparse_launch_us = event_time_us(sparse_all, 4 * nsets, reps)
-    sel_bytes_layer = 2 * (K1 * d_qkv + K2 * d + K3 * 2 * d_ff + K4 * d)
+    standalone_launch_us = sparse_launch_us
+    stage_us = None
+    if B == 1:
+        # The kernel that dominates the timed layer step is the projection with the Top-K fused in
+        # (4 launches per step).  Time it inside larosa_layer_forward itself: the library records
+        # caller-supplied HIP events at the stage boundaries of each (eagerly launched) step.
+        n_ev = max(nsets, min(args.steps, 128))
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(n_ev)]
+        for es in evs:
+            for e in es:
+                e.record()              # creates the underlying hipEvent_t
+        torch.cuda.synchronize()
+        for i in range(nsets):
+            api.layer_forward(layers[i % nsets], x, out, ws)
+        for i in range(n_ev):
+            api.layer_forward(layers[i % nsets], x, out, ws, stage_events=evs[i])
+        torch.cuda.synchronize()
+        names = ["h1_stage", "qkv", "o", "h3_stage", "gu", "down"]
+        stage_us = {n: 0.0 for n in names}
+        for es in evs:
+            for k, n in enumerate(names):
+                stage_us[n] += es[k].elapsed_time(es[k + 1]) * 1e3 / n_ev
+        sparse_launch_us = (stage_us["qkv"] + stage_us["o"] + stage_us["gu"] + stage_us["down"]) / 4.0
+    # rows a launch has to read: the kept rows at batch 1, the union of the tokens' kept rows otherwise
+    U = [int(torch.unique(trace[n]).numel()) for n in ("idx1", "idx2", "idx3", "idx4")]
+    sel_bytes_layer = 2 * (U[0] * d_qkv + U[1] * d + U[2] * 2 * d_ff + U[3] * d)
     sel_bytes_launch = sel_bytes_layer / 4.0
     achieved_gbs = sel_bytes_launch / (sparse_launch_us * 1e-6) / 1e9
 
@@ -192,7 +233,9 @@ def main():
             for s in sets:
                 api.sparse_gemv(s[wn], trace[hn], trace[inn], ys[yn], shape.dtype, ws)
         us = event_time_us(one, nsets, reps)
-        per_proj[yn] = dict(us=round(us, 3), GBs=round(2 * K * dout / (us * 1e-6) / 1e9, 1), K=K, d_out=dout)
+        Un = U[[p_[3] for p_ in proj].index(yn)]
+        per_proj[yn] = dict(us=round(us, 3), GBs=round(2 * Un * dout / (us * 1e-6) / 1e9, 1), K=K, rows_read=Un,
+                            d_out=dout)
 
     # ---- dense comparators on the same GPU: the library's dense mat-vec over the same fused
     # weights (4 launches), and the vendor BLAS through torch (harness-side only)
@@ -280,11 +323,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["workload"] if args.config == 1 and p == 0.4 and B == 1 else
                    f"{cfg['workload']}; batch {B}; sparsity {p}",
-                   "shape": shape.name, "batch": B, "sparsity": p, "K": [K1, K2, K3, K4], "weight_sets": nsets,
+                   "shape": shape.name, "batch": B, "sparsity": p, "K": [K1, K2, K3, K4], "union_rows": U,
+                   "weight_sets": nsets,
                    "launch": "one HIP graph of larosa_layer_forward per weight set"},
         "roofline": {"bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "gemv_rows_kernel (indexed): the 4 column-sparse projections of a layer",
+                     "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, B, p)),
+                     "kernel": ("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step, "
+                                "timed by HIP events recorded inside larosa_layer_forward" if B == 1 else
+                                "skinny_fma/mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
                      "bytes_per_launch": sel_bytes_launch, "us_per_launch": round(sparse_launch_us, 3)},
         "cpu_baseline": cpu,
         "extra": {
@@ -295,6 +342,8 @@ def main():
             "layer_GBs_on_selected_rows": round(sel_bytes_layer / (graph_us * 1e-6) / 1e9, 1),
             "layer_GBs_on_all_bytes": round(all_bytes_layer / (graph_us * 1e-6) / 1e9, 1),
             "sparse_projections_us_per_layer": round(sparse_proj_layer_us, 2),
+            "stage_us_in_layer": None if stage_us is None else {k: round(v, 2) for k, v in stage_us.items()},
+            "standalone_sparse_gemv_us_per_launch": round(standalone_launch_us, 3),
             "per_projection": per_proj,
             "dense_gemv_us_per_layer": round(dense_layer_us, 2),
             "dense_gemv_GBs": round(dense_bytes_layer / (dense_layer_us * 1e-6) / 1e9, 1),

@@ -121,6 +121,11 @@ typedef struct {
 typedef struct {
   void *h1, *qkv, *h2, *o, *x1, *h3, *gu, *h4, *down, *x2;
   int32_t *idx1, *idx2, *idx3, *idx4;
+  /* Optional caller-created hipEvent_t handles (each nullable), recorded on `stream` at the stage
+   * boundaries so a caller can time the stages of one call: [0] on entry, [1] after the h1 stage
+   * (rotation / pre-norm), [2] after q|k|v, [3] after o, [4] after the h3 stage, [5] after gate|up,
+   * [6] after down, [7] after the adapter.  Do not pass events while the stream is being captured. */
+  void* stage_events[8];
 } larosa_trace;
 
 /* Workspace bytes larosa_layer_forward needs for this layer and B tokens (host only). */

@@ -43,7 +43,7 @@ TRACE_FIELDS = ("h1", "qkv", "h2", "o", "x1", "h3", "gu", "h4", "down", "x2", "i
 
 
 class _Trace(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in TRACE_FIELDS]
+    _fields_ = [(n, ctypes.c_void_p) for n in TRACE_FIELDS] + [("stage_events", ctypes.c_void_p * 8)]
 
 
 def lib() -> ctypes.CDLL:
@@ -187,11 +187,17 @@ class Layer:
         return out
 
 
-def layer_forward(layer: Layer, x, x_out, ws: Workspace, trace: dict | None = None):
+def layer_forward(layer: Layer, x, x_out, ws: Workspace, trace: dict | None = None, stage_events=None):
+    """stage_events: optional list of up to 8 torch.cuda.Event(enable_timing=True) that have been
+    recorded once already (so their handles exist); the library records them at stage boundaries."""
     B = x.shape[0]
     tr = None
-    if trace is not None:
+    if trace is not None or stage_events is not None:
+        trace = trace or {}
         tr = _Trace(*[None if trace.get(n) is None else trace[n].data_ptr() for n in TRACE_FIELDS])
+        if stage_events is not None:
+            for i, ev in enumerate(stage_events[:8]):
+                tr.stage_events[i] = None if ev is None else ev.cuda_event
     _check(lib().larosa_layer_forward(ctypes.byref(layer.c), _ptr(x), _ptr(x_out), B,
                                       ctypes.byref(tr) if tr is not None else None,
                                       ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_layer_forward")

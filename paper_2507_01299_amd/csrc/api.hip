@@ -358,6 +358,10 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     return run_gemv(a, bf, ws, gws, st);
   };
 
+  auto mark = [&](int i) {
+    if (T.stage_events[i]) (void)hipEventRecord(static_cast<hipEvent_t>(T.stage_events[i]), st);
+  };
+  mark(0);
   if (B > 1) {
     // Batched decode: per-token Top-K writes each token's activations with the dropped channels
     // zeroed, and one pass over all weight rows serves every token (the union of the index sets).
@@ -371,17 +375,23 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       return run_batched(a, bf, ws, gws, st);
     };
     LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
+    mark(1);
     LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, masked, st));
     LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr));
+    mark(2);
     LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
     LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, masked, st));
     LAROSA_TRY(project(L->Wo, d_q, d, x1, x, o));
+    mark(3);
     LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
+    mark(4);
     LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, masked, st));
     LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr));
+    mark(5);
     LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
     LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, masked, st));
     LAROSA_TRY(project(L->Wdown, d_ff, d, x2, x1, down));
+    mark(6);
   } else if (tuning().fused) {
     // Top-K fused into the projections: 4 projection kernels (+ one rotation each when Q is given)
     auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
@@ -403,32 +413,44 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
                      uint16_t* y, int d_out, int K, int32_t* idx_traced) -> int {
       if (Q) {
         if (int rc = block_input(src, Q, scale, h)) return rc;
+        mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
         return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr);
       }
+      mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
       return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
                    static_cast<uint16_t*>(h_traced), idx_traced, scale);
     };
     LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1));
+    mark(2);
     LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, x, static_cast<uint16_t*>(T.o),
                      static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
+    mark(3);
     LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3));
+    mark(5);
     LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, x1, static_cast<uint16_t*>(T.down),
                      static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
+    mark(6);
   } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
   LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
+  mark(1);
   LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wqkv, h1, idx1, qkv, d, d_qkv, L->K1, nullptr, nullptr));
+  mark(2);
   LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
   LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, x, o));
+  mark(3);
   // MLP block: h3 -> gate|up -> h4 -> down -> + residual
   LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
+  mark(4);
   LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wgu, h3, idx3, gu, d, 2 * d_ff, L->K3, nullptr, nullptr));
+  mark(5);
   LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
   LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+  mark(6);
   }
   // residual adapter
   if (L->adapter && B > 1) {
@@ -446,6 +468,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   } else if (T.x2) {
     LAROSA_HIP(launch_copy_u16(x2, static_cast<uint16_t*>(T.x2), Bz * d, st));
   }
+  mark(7);
 #undef LAROSA_TRY
 #undef LAROSA_HIP
   return LAROSA_OK;
