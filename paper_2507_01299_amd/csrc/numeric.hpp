@@ -77,13 +77,18 @@ __device__ __forceinline__ int wave_sum_i(int v) {
   return v;
 }
 
-// inclusive prefix sum across the 64 lanes of a wave
-__device__ __forceinline__ unsigned wave_scan_inclusive(unsigned v, int lane) {
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    unsigned n = __shfl_up(v, o, kWave);
-    if (lane >= o) v += n;
-  }
+// inclusive prefix sum across the 64 lanes of a wave, on the data-parallel-primitive path of the
+// VALU (no LDS round trips): Hillis-Steele steps of 1, 2, 4, 8 lanes inside each row of 16, then
+// the row totals are carried into the following rows by the two row-broadcast steps.
+__device__ __forceinline__ unsigned wave_scan_inclusive(unsigned v, int /*lane*/) {
+  // dpp_ctrl: row_shr:n = 0x110 + n, row_bcast:15 = 0x142, row_bcast:31 = 0x143.  old = 0 with
+  // bound_ctrl off: lanes whose source lies outside the row (or outside row_mask) add zero.
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xA, 0xF, false);   // lane 15 of rows 0, 2 -> rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xC, 0xF, false);   // lane 31 -> rows 2, 3
   return v;
 }
 

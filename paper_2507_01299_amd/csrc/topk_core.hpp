@@ -19,37 +19,10 @@ namespace larosa {
 template <int NW>
 struct TopkShared {
   unsigned hist_w[NW][256];
-  unsigned hist[256];
   unsigned wave_tot[NW];
-  int bin;
-  unsigned above;
+  int bin, bin2;            // pass-1 / pass-2 bin holding the K-th largest key
+  unsigned above, above2;   // counts strictly above those bins
 };
-
-// Over bins visited from the highest down, find the first bin at which the running count
-// reaches `need`.  Executed by one wave; each lane covers NB/64 bins.
-template <int NB>
-__device__ __forceinline__ void locate_bin(const unsigned* hist, unsigned need, int lane, int* out_bin,
-                                           unsigned* out_above) {
-  constexpr int PER = NB / 64;
-  unsigned c[PER];
-  unsigned local = 0;
-#pragma unroll
-  for (int q = 0; q < PER; ++q) {
-    c[q] = hist[NB - 1 - (lane * PER + q)];   // position lane*PER+q counts from the top bin
-    local += c[q];
-  }
-  const unsigned incl = wave_scan_inclusive(local, lane);
-  unsigned run = incl - local;
-#pragma unroll
-  for (int q = 0; q < PER; ++q) {
-    const unsigned before = run;
-    run += c[q];
-    if (before < need && run >= need) {
-      *out_bin = NB - 1 - (lane * PER + q);
-      *out_above = before;
-    }
-  }
-}
 
 // Selection state of one lane after block_select.
 struct TopkLane {
@@ -71,27 +44,44 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  unsigned* flat = &sm.hist_w[0][0];
+  unsigned* flat = &sm.hist_w[0][0];   // NW x 256 words: pass 1 uses all, pass 2 the first NW x 128
 
+  // ---- pass 1: top 8 key bits
   for (int i = tid; i < NW * 256; i += NT) flat[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < E; ++q)
     if (q < nvalid) atomicAdd(&sm.hist_w[wave][(raw[q] & 0x7FFFu) >> 7], 1u);
   __syncthreads();
-  if (tid < 256) {
-    unsigned s = 0;
+  if (wave == 0) {
+    // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p
+    unsigned c[4], local = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += sm.hist_w[w][tid];
-    sm.hist[tid] = s;
+    for (int q = 0; q < 4; ++q) {
+      const int bin = 255 - (lane * 4 + q);
+      unsigned t = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) t += sm.hist_w[w][bin];
+      c[q] = t;
+      local += t;
+    }
+    const unsigned need = static_cast<unsigned>(K);
+    unsigned run = wave_scan_inclusive(local, lane) - local;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const unsigned before = run;
+      run += c[q];
+      if (before < need && run >= need) {
+        sm.bin = 255 - (lane * 4 + q);
+        sm.above = before;
+      }
+    }
   }
-  __syncthreads();
-  if (wave == 0) locate_bin<256>(sm.hist, static_cast<unsigned>(K), lane, &sm.bin, &sm.above);
   __syncthreads();
   const int bin1 = sm.bin;
   const unsigned above1 = sm.above;
-  __syncthreads();
 
+  // ---- pass 2: low 7 bits inside bin1 (the pass-1 reads of hist_w are complete: wave 0 passed the barrier)
   for (int i = tid; i < NW * 128; i += NT) flat[i] = 0u;
   __syncthreads();
 #pragma unroll
@@ -100,18 +90,33 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
     if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&flat[wave * 128 + (key & 127u)], 1u);
   }
   __syncthreads();
-  if (tid < 128) {
-    unsigned s = 0;
+  if (wave == 0) {
+    unsigned c[2], local = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += flat[w * 128 + tid];
-    sm.hist[tid] = s;
+    for (int q = 0; q < 2; ++q) {
+      const int bin = 127 - (lane * 2 + q);
+      unsigned t = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) t += flat[w * 128 + bin];
+      c[q] = t;
+      local += t;
+    }
+    const unsigned need = static_cast<unsigned>(K) - above1;
+    unsigned run = wave_scan_inclusive(local, lane) - local;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const unsigned before = run;
+      run += c[q];
+      if (before < need && run >= need) {
+        sm.bin2 = 127 - (lane * 2 + q);
+        sm.above2 = before;
+      }
+    }
   }
   __syncthreads();
-  if (wave == 0) locate_bin<128>(sm.hist, static_cast<unsigned>(K) - above1, lane, &sm.bin, &sm.above);
-  __syncthreads();
   TopkLane out;
-  out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(sm.bin);
-  out.r = static_cast<unsigned>(K) - (above1 + sm.above);
+  out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(sm.bin2);
+  out.r = static_cast<unsigned>(K) - (above1 + sm.above2);
 
   unsigned n_gt = 0, n_eq = 0;
 #pragma unroll
