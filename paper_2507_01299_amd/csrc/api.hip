@@ -14,6 +14,7 @@ constexpr size_t kCounterSlots = 4096;                        // arrival counter
 constexpr size_t kCounterWords = kCounterSlots * kCounterStride;
 constexpr size_t kCounterBytes = kCounterWords * sizeof(unsigned);
 constexpr int kMaxTopkD = 32768;
+constexpr int kFusedMaxWidth = 16384;   // widest block input selected inside every projection workgroup
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -427,8 +428,15 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     mark(3);
     LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3));
     mark(5);
-    LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, x1, static_cast<uint16_t*>(T.down),
-                     static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
+    if (d_ff <= kFusedMaxWidth) {
+      LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, x1, static_cast<uint16_t*>(T.down),
+                       static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
+    } else {
+      // a wide intermediate vector makes the per-workgroup selection too long: select once instead
+      LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
+      LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
+      LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+    }
     mark(6);
   } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
