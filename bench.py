@@ -44,11 +44,6 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def kept(d, p):
-    import math
-    return max(1, min(d, int(math.floor((1.0 - p) * d + 1e-9))))
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +53,8 @@ def main():
     ap.add_argument("--sparsity", type=float, default=0.4)
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--nsets", type=int, default=8)
+    ap.add_argument("--alpha", default="1.0,1.0", metavar="A1,A3",
+                    help="sparsity coefficients of h1 and h3 (h2, h4 follow from the block constraints)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--detail", default=None, help="also write the full report to this JSON file")
@@ -89,7 +86,9 @@ def main():
     td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
     p, B, nsets = args.sparsity, args.batch, max(1, args.nsets)
     d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff
-    K1, K2, K3, K4 = kept(d, p), kept(d_q, p), kept(d, p), kept(d_ff, p)
+    from paper_2507_01299_amd import allocation
+    alpha1, alpha3 = (float(v) for v in args.alpha.split(","))
+    K1, K2, K3, K4 = allocation.kept_counts(d, d_q, d_ff, p, alpha1, alpha3)
     d_qkv = d_q + 2 * d_kv
 
     # ---- weight set 0: the canonical synthetic layer (seeded numpy draws, PCA rotations)
@@ -321,14 +320,14 @@ def main():
         "vs_baseline": None,
         "dtype": shape.dtype,
         "data": "synthetic",
-        "config": {"workload": cfg["workload"] if args.config == 1 and p == 0.4 and B == 1 else
-                   f"{cfg['workload']}; batch {B}; sparsity {p}",
+        "config": {"workload": cfg["workload"] if args.config == 1 and p == 0.4 and B == 1 and args.alpha == "1.0,1.0"
+                   else f"{cfg['workload']}; batch {B}; sparsity {p}; alpha1,alpha3 = {args.alpha}",
                    "shape": shape.name, "batch": B, "sparsity": p, "K": [K1, K2, K3, K4], "union_rows": U,
                    "weight_sets": nsets,
                    "launch": "one HIP graph of larosa_layer_forward per weight set"},
         "roofline": {"bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, B, p)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, B, p)) if args.alpha == "1.0,1.0" else None,
                      "kernel": ("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step, "
                                 "timed by HIP events recorded inside larosa_layer_forward" if B == 1 else
                                 "skinny_fma/mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
