@@ -41,7 +41,7 @@ size_t batched_partial_bytes(const GemvPlan& p, int B, bool coef_scale) {
 
 // One launch of the batched kernels (B > 1): C holds the tokens' coefficients over all rows.
 int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
-  const GemvPlan p = plan_batched(a.d_in, a.d_out);
+  const GemvPlan p = plan_batched(a.d_in, a.d_out, batched_uses_mfma(a.B, a.coef_scale != nullptr));
   const int tpg = batched_tokens_per_group(a.B, a.coef_scale != nullptr);
   const size_t groups = (a.B + tpg - 1) / tpg;
   if (groups * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
@@ -184,7 +184,7 @@ int larosa_sparse_gemv(const void* Wp, const void* h, const int32_t* idx, void* 
   if (int rc = check_gemv_shapes(B, d_in, d_out, K)) return rc;
   if (B > 1) {
     // masked coefficient matrix in the tail of the workspace, then one pass over the weight
-    const GemvPlan p = plan_batched(d_in, d_out);
+    const GemvPlan p = plan_batched(d_in, d_out, batched_uses_mfma(B, false));
     const size_t head = round_up(kCounterBytes + batched_partial_bytes(p, B, false), 256);
     const size_t cbytes = static_cast<size_t>(B) * d_in * 2;
     if (!ws || !aligned(ws, 256) || ws_bytes < head + cbytes) return LAROSA_EWORKSPACE;
@@ -243,11 +243,15 @@ static size_t layer_gemv_ws(const larosa_layer* L, int B) {
   }
   if (B > 1) {
     const bool cs = L->rms_attn || L->rms_mlp;
-    const GemvPlan bp[] = {plan_batched(L->d, L->d), plan_batched(L->d, L->d_q + 2 * L->d_kv),
-                           plan_batched(L->d_q, L->d), plan_batched(L->d, 2 * L->d_ff), plan_batched(L->d_ff, L->d)};
-    for (const GemvPlan& p : bp) {
-      const size_t need = round_up(kCounterBytes + batched_partial_bytes(p, B, cs), 256);
-      if (need > s) s = need;
+    for (int mf = 0; mf < 2; ++mf) {
+      const bool m = mf != 0;
+      const GemvPlan bp[] = {plan_batched(L->d, L->d, m), plan_batched(L->d, L->d_q + 2 * L->d_kv, m),
+                             plan_batched(L->d_q, L->d, m), plan_batched(L->d, 2 * L->d_ff, m),
+                             plan_batched(L->d_ff, L->d, m)};
+      for (const GemvPlan& p : bp) {
+        const size_t need = round_up(kCounterBytes + batched_partial_bytes(p, B, m ? false : cs), 256);
+        if (need > s) s = need;
+      }
     }
   }
   return s;

@@ -284,20 +284,23 @@ __device__ __forceinline__ float4_t mfma16<BF16>(uint2 a, uint2 b, float4_t c) {
                                                    0, 0);
 }
 
-constexpr int kTileStride = 516;   // floats per token row of the LDS strip tile (16-byte aligned, off the bank period)
+constexpr int kMStrip = 128;        // output columns per workgroup of the matrix-core kernel
+constexpr int kMRW = 8;             // its row-waves
+constexpr int kMTileStride = 130;   // floats per token row of an LDS tile (8-byte aligned, spreads tokens over banks)
 
+// Geometry: a workgroup is 8 waves on ONE strip of 128 columns (256 contiguous bytes per row), each
+// wave taking its own run of 16-row tiles, two tiles (8 row loads of 16 bytes per lane) in flight.
+// Narrow strips keep the number of workgroups that share a strip -- and with it the partial-sum
+// traffic, which grows with the token count -- small.
 template <typename T, int NTB>
 __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
-  constexpr int RWM = 2;   // row-waves; 4 column-waves of 128 columns each
-  __shared__ float tile[16][kTileStride];
+  __shared__ float tile[4][16][kMTileStride];
   __shared__ float scale_s[NTB * 16];
   __shared__ int s_last;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int cwm = wave & 3;
-  const int rwm = wave >> 2;
+  const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kgrp = lane >> 4;    // K-run of 4 rows inside a 16-row tile
   const int m = lane & 15;       // column group (A operand) / token (B operand)
   const int g = blockIdx.x;
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
     const int t1 = min(K, t0 + (f1 - f0));
     const int n = t1 - t0;
     const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
-    const int colbase = s * kStripCols + cwm * 128 + 8 * m;   // this lane's 8 columns (A operand)
+    const int colbase = s * kMStrip + 8 * m;   // this lane's 8 columns (A operand)
     const bool colv = colbase < a.d_out;
 
     float4_t acc[NTB][8];
@@ -325,111 +328,137 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
       for (int i = 0; i < 8; ++i) acc[tb][i] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     const int ntiles = (n + 15) / 16;
-    const int per = (ntiles + RWM - 1) / RWM;
-    const int tl0 = rwm * per;
+    const int per = (ntiles + kMRW - 1) / kMRW;
+    const int tl0 = rw * per;
     const int tl1 = min(ntiles, tl0 + per);
-    for (int tl = tl0; tl < tl1; ++tl) {
-      const int j0 = t0 + tl * 16 + 4 * kgrp;        // first of this lane's 4 rows; t0 % 8 == 0, so j0 % 4 == 0
-      uint4 v[4];
+    for (int tl = tl0; tl < tl1; tl += 2) {
+      uint4 v[2][4];
+      uint2 bf[2][NTB];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r = min(j0 + q, t1 - 1);
-        v[q] = colv ? load_stream16(a.W + static_cast<size_t>(r) * a.d_out + colbase) : make_uint4(0u, 0u, 0u, 0u);
+      for (int h2 = 0; h2 < 2; ++h2) {
+        // first of this lane's 4 rows; t0 % 8 == 0, so j0 % 4 == 0.  A tile past this wave's run
+        // starts at t1: its rows clamp to a valid address and its B operand is zero.
+        const int j0 = (tl + h2 < tl1) ? t0 + (tl + h2) * 16 + 4 * kgrp : t1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int r = min(j0 + q, t1 - 1);
+          v[h2][q] = colv ? load_stream16(a.W + static_cast<size_t>(r) * a.d_out + colbase) : make_uint4(0u, 0u, 0u, 0u);
+        }
+        // B operand: 4 consecutive rows of token (b0 + tb*16 + m); rows at or past t1 belong to
+        // another workgroup (or do not exist) and must contribute nothing
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) {
+          const int tok = b0 + tb * 16 + m;
+          uint2 c = make_uint2(0u, 0u);
+          if (tok < a.B && j0 < t1) c = *reinterpret_cast<const uint2*>(a.C + static_cast<size_t>(tok) * K + j0);
+          if (j0 + 1 >= t1) c.x &= 0x0000FFFFu;
+          if (j0 + 2 >= t1) c.y = 0u;
+          if (j0 + 3 >= t1) c.y &= 0x0000FFFFu;
+          if (j0 >= t1) c.x = 0u;
+          bf[h2][tb] = c;
+        }
       }
-      // B operand: 4 consecutive rows of token (b0 + tb*16 + m); rows at or past t1 belong to
-      // another workgroup (or do not exist) and must contribute nothing
-      uint2 bf[NTB];
 #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) {
-        const int tok = b0 + tb * 16 + m;
-        uint2 c = make_uint2(0u, 0u);
-        if (tok < a.B && j0 < t1) c = *reinterpret_cast<const uint2*>(a.C + static_cast<size_t>(tok) * K + j0);
-        if (j0 + 1 >= t1) c.x &= 0x0000FFFFu;
-        if (j0 + 2 >= t1) c.y = 0u;
-        if (j0 + 3 >= t1) c.y &= 0x0000FFFFu;
-        if (j0 >= t1) c.x = 0u;
-        bf[tb] = c;
-      }
-      // A operand for column offset i: element i of each of the 4 row registers
-      const uint32_t* vw0 = reinterpret_cast<const uint32_t*>(&v[0]);
-      const uint32_t* vw1 = reinterpret_cast<const uint32_t*>(&v[1]);
-      const uint32_t* vw2 = reinterpret_cast<const uint32_t*>(&v[2]);
-      const uint32_t* vw3 = reinterpret_cast<const uint32_t*>(&v[3]);
+      for (int h2 = 0; h2 < 2; ++h2) {
+        // A operand for column offset i: element i of each of the 4 row registers
+        const uint32_t* vw0 = reinterpret_cast<const uint32_t*>(&v[h2][0]);
+        const uint32_t* vw1 = reinterpret_cast<const uint32_t*>(&v[h2][1]);
+        const uint32_t* vw2 = reinterpret_cast<const uint32_t*>(&v[h2][2]);
+        const uint32_t* vw3 = reinterpret_cast<const uint32_t*>(&v[h2][3]);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        uint2 af;
-        af.x = __builtin_amdgcn_perm(vw1[i >> 1], vw0[i >> 1], sel);
-        af.y = __builtin_amdgcn_perm(vw3[i >> 1], vw2[i >> 1], sel);
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+          uint2 af;
+          af.x = __builtin_amdgcn_perm(vw1[i >> 1], vw0[i >> 1], sel);
+          af.y = __builtin_amdgcn_perm(vw3[i >> 1], vw2[i >> 1], sel);
 #pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) acc[tb][i] = mfma16<T>(af, bf[tb], acc[tb][i]);
+          for (int tb = 0; tb < NTB; ++tb) acc[tb][i] = mfma16<T>(af, bf[h2][tb], acc[tb][i]);
+        }
       }
     }
 
     const int n_s = ge.g_last - ge.g_first + 1;
-    const size_t slot_floats = static_cast<size_t>(NTB) * 16 * kStripCols;
+    const size_t slot_floats = static_cast<size_t>(NTB) * 16 * kMStrip;
     unsigned long long* slot = reinterpret_cast<unsigned long long*>(
         a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
     unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
 
-    // Per token block: sum the two row-waves into the LDS tile [token][512 columns]; D element e of
-    // MFMA i in lane (kgrp, m) is column cwm*128 + 32*kgrp + 8*e + i of token m.
-    auto tile_pass = [&](int tb, bool to_global) {
+    // Sum the 8 row-waves of token block tb: waves 0-3 write their tiles, waves 4-7 add theirs on
+    // top, then every thread adds the four tiles for its two float pairs (pair q: token q / 64,
+    // columns 2*(q % 64), +1).  D element e of MFMA i in lane (kgrp, m) is column 32*kgrp + 8*e + i
+    // of token m.  The order of the additions is fixed.
+    auto reduce_tb = [&](int tb, float2 (&sm)[2]) {
 #pragma unroll
-      for (int r = 0; r < RWM; ++r) {
-        if (rwm == r) {
+      for (int r = 0; r < 2; ++r) {
+        if ((rw >> 2) == r) {
 #pragma unroll
           for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              float* p = &tile[m][cwm * 128 + 32 * kgrp + 8 * e + i];
+              float* p = &tile[rw & 3][m][32 * kgrp + 8 * e + i];
               *p = (r == 0) ? acc[tb][i][e] : *p + acc[tb][i][e];
             }
         }
         __syncthreads();
       }
-      if (to_global) {
-        // 16 x 512 floats = 4096 float pairs, 8 per thread, each store instruction 512 contiguous bytes
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const int q = tid + k * kBThreads;          // pair index: token = q / 256, pair in row = q % 256
-          const float2 pr = *reinterpret_cast<const float2*>(&tile[q >> 8][(q & 255) * 2]);
-          const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(pr.x)) |
-                                       (static_cast<unsigned long long>(__float_as_uint(pr.y)) << 32);
-          __hip_atomic_store(slot + static_cast<size_t>(tb) * 4096 + q, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();
-      }
-    };
-    // epilogue of one token block from the LDS tile: 16 tokens x 64 column groups of 8
-    auto tile_out = [&](int tb) {
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
-        const int gid = tid + k * kBThreads;
-        const int tok = b0 + tb * 16 + (gid >> 6);
-        const int col = s * kStripCols + (gid & 63) * 8;
+        const int q = tid + k * kBThreads;
+        float2 t = *reinterpret_cast<const float2*>(&tile[0][q >> 6][(q & 63) * 2]);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+          const float2 u = *reinterpret_cast<const float2*>(&tile[w][q >> 6][(q & 63) * 2]);
+          t.x += u.x;
+          t.y += u.y;
+        }
+        sm[k] = t;
+      }
+      __syncthreads();
+    };
+    // epilogue of one token block: its 16 x 128 sums (pairs held as in reduce_tb) go through tile[0]
+    auto tile_out = [&](int tb, const float2 (&sm)[2]) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int q = tid + k * kBThreads;
+        *reinterpret_cast<float2*>(&tile[0][q >> 6][(q & 63) * 2]) = sm[k];
+      }
+      __syncthreads();
+      if (tid < 256) {
+        const int tok = b0 + tb * 16 + (tid >> 4);
+        const int col = s * kMStrip + (tid & 15) * 8;
         if (tok < a.B && col < a.d_out) {
           float v[8];
-          const float* p = &tile[gid >> 6][(gid & 63) * 8];
+          const float* p = &tile[0][tid >> 4][(tid & 15) * 8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] = p[e];
-          store_out8<T>(a, tok, col, v, scale_s[tb * 16 + (gid >> 6)]);
+          store_out8<T>(a, tok, col, v, scale_s[tb * 16 + (tid >> 4)]);
         }
       }
       __syncthreads();
     };
 
     if (n_s == 1) {
-      token_scales<T, 8>(a, b0, NTB * 16, scale_s, lane, wave);
+      token_scales<T, kMRW>(a, b0, NTB * 16, scale_s, lane, rw);
       __syncthreads();
 #pragma unroll
       for (int tb = 0; tb < NTB; ++tb) {
-        tile_pass(tb, false);
-        tile_out(tb);
+        float2 sm[2];
+        reduce_tb(tb, sm);
+        tile_out(tb, sm);
       }
     } else {
 #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) tile_pass(tb, true);
+      for (int tb = 0; tb < NTB; ++tb) {
+        float2 sm[2];
+        reduce_tb(tb, sm);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(sm[k].x)) |
+                                       (static_cast<unsigned long long>(__float_as_uint(sm[k].y)) << 32);
+          __hip_atomic_store(slot + static_cast<size_t>(tb) * 1024 + tid + k * kBThreads, v, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
       if (tid == 0) {
@@ -439,43 +468,36 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
       __syncthreads();
       if (s_last != 0) {   // uniform over the workgroup
         if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        token_scales<T, 8>(a, b0, NTB * 16, scale_s, lane, wave);
+        token_scales<T, kMRW>(a, b0, NTB * 16, scale_s, lane, rw);
         for (int tb = 0; tb < NTB; ++tb) {
-          // each thread owns 8 float pairs of the block and adds the partials in workgroup order
-          float2 sum[8];
+          // each thread owns 2 float pairs of the block and adds the partials in workgroup order
+          float2 sum[2];
+          sum[0] = sum[1] = make_float2(0.f, 0.f);
+          for (int gg = ge.g_first; gg <= ge.g_last; gg += 8) {
+            unsigned long long v[8][2];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) sum[k] = make_float2(0.f, 0.f);
-          for (int gg = ge.g_first; gg <= ge.g_last; gg += 2) {
-            unsigned long long v[2][8];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < 8; ++q) {
               const int g2 = min(gg + q, ge.g_last);
               const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
               const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
                   a.partial + ((static_cast<size_t>(grp) * a.G + g2) * 2 + sgn) * slot_floats);
 #pragma unroll
-              for (int k = 0; k < 8; ++k)
-                v[q][k] = __hip_atomic_load(p + static_cast<size_t>(tb) * 4096 + tid + k * kBThreads, __ATOMIC_RELAXED,
+              for (int k = 0; k < 2; ++k)
+                v[q][k] = __hip_atomic_load(p + static_cast<size_t>(tb) * 1024 + tid + k * kBThreads, __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);
             }
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < 8; ++q) {
               if (gg + q <= ge.g_last) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
+                for (int k = 0; k < 2; ++k) {
                   sum[k].x += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
                   sum[k].y += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
                 }
               }
             }
           }
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const int q = tid + k * kBThreads;
-            *reinterpret_cast<float2*>(&tile[q >> 8][(q & 255) * 2]) = sum[k];
-          }
-          __syncthreads();
-          tile_out(tb);
+          tile_out(tb, sum);
         }
       }
     }
@@ -507,26 +529,28 @@ hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
 
 }  // namespace
 
+bool batched_uses_mfma(int B, bool coef_scale) { return B > 4 && !coef_scale; }
+
 int batched_tokens_per_group(int B, bool coef_scale) {
   if (B <= 2) return 2;
-  if (B <= 4 || coef_scale) return 4;
+  if (!batched_uses_mfma(B, coef_scale)) return 4;
   return B <= 16 ? 16 : 32;
 }
 
-GemvPlan plan_batched(int d_in, int d_out) {
+GemvPlan plan_batched(int d_in, int d_out, bool mfma) {
   GemvPlan p;
-  p.strip_cols = kStripCols;
-  p.nstrips = (d_out + kStripCols - 1) / kStripCols;
+  p.strip_cols = mfma ? kMStrip : kStripCols;
+  p.nstrips = (d_out + p.strip_cols - 1) / p.strip_cols;
   const long T = static_cast<long>(p.nstrips) * d_in;
   long G = tuning().g_target > 0 ? tuning().g_target : 256;     // one workgroup per compute unit
   if (G < p.nstrips) G = p.nstrips;
   long chunk = (T + G - 1) / G;
   chunk = (chunk + 15) / 16 * 16;                                // whole 16-row tiles; keeps row starts 8-aligned
-  if (chunk > kBatchChunkMax) chunk = kBatchChunkMax;
+  if (!mfma && chunk > kBatchChunkMax) chunk = kBatchChunkMax;   // LDS staging of the coefficients
   if (chunk > d_in) chunk = d_in;                                // a workgroup touches at most two strips
   p.chunk = static_cast<int>(chunk);
   p.G = static_cast<int>((T + chunk - 1) / chunk);
-  p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;  // per token
+  p.partial_floats = static_cast<size_t>(p.G) * 2 * p.strip_cols;  // per token
   return p;
 }
 

@@ -83,7 +83,8 @@ struct BatchArgs {
   uint16_t* y_pre;
 };
 constexpr int kBatchChunkMax = 1024;   // rows per workgroup segment (LDS coefficient staging)
-GemvPlan plan_batched(int d_in, int d_out);
+GemvPlan plan_batched(int d_in, int d_out, bool mfma);
+bool batched_uses_mfma(int B, bool coef_scale);
 int batched_tokens_per_group(int B, bool coef_scale);
 hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s);
 // C[b,:] = 0 except C[b, idx[b,t]] = h[b, idx[b,t]]
