@@ -5,12 +5,17 @@
 //     y[b,:] = sum_j C[b,j] * W[j,:],   C[b,j] = h[b,j] if j in idx_b else 0.
 // The same kernels serve the batched rotation / adapter / dense baseline (C = x).
 //
-//   * up to 4 tokens: plain fp32 FMAs, one 16-byte row piece per lane feeds every token;
-//   * 5..32 tokens: the tile really is a dense contraction, so it goes to the matrix cores
-//     (v_mfma_f32_16x16x16 f16/bf16): M = 16 output columns, N = 16 tokens, K = 16 rows.
-//     A lane loads 8 consecutive columns of 4 rows (16 lanes x 16 bytes = 256 contiguous bytes per
-//     row), and a byte permute regroups those registers into the K-runs the instruction wants;
-//     no LDS staging of the weight is needed.
+//   * the product is a skinny dense contraction (all rows x B tokens), so it runs on the matrix
+//     cores (v_mfma_f32_16x16x16 f16/bf16): M = 16 output columns, N = 16 tokens, K = 16 rows,
+//     token blocks padded to 16.  A lane loads 8 consecutive columns of 4 rows (16 lanes x 16 bytes
+//     = 256 contiguous bytes per row), and a byte permute regroups those registers into the K-runs
+//     the instruction wants; the weight never passes through LDS.  Measured on MI355X this kernel is
+//     the fastest for every B >= 2 (LLaMA3-8B layer: 160 us at B = 2 and 4, 173 us at B = 16; the
+//     fp32-FMA kernel needs 205 us at B = 4), because the kernel is HBM-bound and the FMA variant
+//     spends its issue slots on B x 8 multiply-adds and coefficient reads per 16 bytes loaded;
+//   * an fp32-FMA kernel (2 or 4 tokens per workgroup) remains for the one case the 16-bit B
+//     operand cannot express: a per-channel coefficient scale applied in fp32 (learned pre-norm
+//     scale in front of an explicit rotation).
 // Work split, cross-workgroup hand-off and epilogue follow the single-token kernel
 // (gemv_core.hpp), with one arrival per workgroup for all its tokens.
 #include "gemv_core.hpp"
@@ -90,16 +95,25 @@ __device__ __forceinline__ void store_out8(const BatchArgs& a, int tok, int col,
 // ------------------------------------------------------------------------------------------------
 // FMA kernel, NB <= 4 tokens per workgroup
 // ------------------------------------------------------------------------------------------------
+// Geometry: a workgroup is 8 waves on ONE strip of 128 columns.  Lane (kgrp, m) = (lane / 16,
+// lane % 16) owns columns 8m..8m+7 of the strip; one load instruction of a wave covers 4 rows (one
+// per kgrp), 256 contiguous bytes each, and 8 such loads are in flight.  The four row groups of a
+// wave are summed by two lane exchanges, the 8 waves through LDS, workgroups through the workspace.
+// Narrow strips keep the number of workgroups per strip, and so the partial-sum traffic, small.
+constexpr int kFStrip = 128;
+
 template <typename T, int NB>
 __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
   __shared__ float coef[NB][kBatchChunkMax];
-  __shared__ float red[kBRW - 1][8][64];
+  __shared__ float red[kBRW - 1][NB][8][16];
   __shared__ float scale_s[NB];
   __shared__ int s_last;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kgrp = lane >> 4;
+  const int m = lane & 15;
   const int g = blockIdx.x;
   const int grp = blockIdx.y;
   const int b0 = grp * NB;
@@ -115,7 +129,7 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
     const int t1 = min(K, t0 + (f1 - f0));
     const int n = t1 - t0;
     const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
-    const int col = s * kStripCols + lane * 8;
+    const int col = s * kFStrip + m * 8;
     const bool colv = col < a.d_out;
 
     // this segment's coefficients, as floats, for the NB tokens
@@ -142,16 +156,18 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
     const int re = min(t1, ra + per);
     if (colv) {
       const uint16_t* wcol = a.W + col;
-      for (int t = ra; t < re; t += kUnroll) {
+      for (int t = ra; t < re; t += 4 * kUnroll) {
         uint4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = load_stream16(wcol + static_cast<size_t>(min(t + u, re - 1)) * a.d_out);
+        for (int u = 0; u < kUnroll; ++u)
+          v[u] = load_stream16(wcol + static_cast<size_t>(min(t + 4 * u + kgrp, re - 1)) * a.d_out);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
           float w[8];
           unpack8<T>(v[u], w);
-          const bool ok = t + u < re;
-          const int ti = min(t + u, re - 1) - t0;
+          const int r = t + 4 * u + kgrp;
+          const bool ok = r < re;
+          const int ti = min(r, re - 1) - t0;
 #pragma unroll
           for (int bb = 0; bb < NB; ++bb) {
             const float c = ok ? coef[bb][ti] : 0.f;
@@ -161,39 +177,46 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
         }
       }
     }
-
-    // row-waves -> one strip partial per token
+    // the four row groups of the wave (fixed order), then the 8 waves through LDS
 #pragma unroll
-    for (int bb = 0; bb < NB; ++bb) {
-      if (rw > 0) {
+    for (int bb = 0; bb < NB; ++bb)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) red[rw - 1][k][lane] = acc[bb][k];
+      for (int k = 0; k < 8; ++k) {
+        acc[bb][k] += __shfl_xor(acc[bb][k], 16, kWave);
+        acc[bb][k] += __shfl_xor(acc[bb][k], 32, kWave);
       }
-      __syncthreads();
-      if (rw == 0) {
-        for (int r = 0; r < kBRW - 1; ++r) {
+    if (rw > 0 && kgrp == 0) {
 #pragma unroll
-          for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][k][lane];
-        }
-      }
-      __syncthreads();
+      for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) red[rw - 1][bb][k][m] = acc[bb][k];
     }
+    __syncthreads();
+    if (rw == 0 && kgrp == 0) {
+      for (int r = 0; r < kBRW - 1; ++r)
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][bb][k][m];
+    }
+    __syncthreads();
 
     const int n_s = ge.g_last - ge.g_first + 1;
     bool last = (n_s == 1);
     if (n_s > 1) {
-      const size_t slot_floats = static_cast<size_t>(NB) * kStripCols;
+      // slot: [NB][4][16] float pairs; lane m of the first wave holds columns 8m..8m+7
+      const size_t slot_floats = static_cast<size_t>(NB) * kFStrip;
       unsigned long long* slot = reinterpret_cast<unsigned long long*>(
           a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
       unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
-      if (rw == 0) {
+      if (rw == 0 && kgrp == 0) {
 #pragma unroll
         for (int bb = 0; bb < NB; ++bb)
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(acc[bb][2 * k])) |
                                          (static_cast<unsigned long long>(__float_as_uint(acc[bb][2 * k + 1])) << 32);
-            __hip_atomic_store(slot + bb * 256 + k * 64 + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slot + bb * 64 + k * 16 + m, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -206,52 +229,57 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
       last = (s_last != 0);
       if (last) {
         if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // lane group kgrp of wave rw adds partials g_first + 4*rw + kgrp, + 32, ...: 32 partials per pass
 #pragma unroll
-        for (int bb = 0; bb < NB; ++bb) {
+        for (int bb = 0; bb < NB; ++bb)
 #pragma unroll
           for (int k = 0; k < 8; ++k) acc[bb][k] = 0.f;
-          for (int gg = ge.g_first + rw; gg <= ge.g_last; gg += 4 * kBRW) {
-            unsigned long long v[4][4];
+        for (int gg = ge.g_first + 4 * rw + kgrp; gg <= ge.g_last; gg += 4 * kBRW) {
+          const int sgn = ((gg * chunk) / K != s) ? 1 : 0;
+          const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
+              a.partial + ((static_cast<size_t>(grp) * a.G + gg) * 2 + sgn) * slot_floats);
+          unsigned long long v[NB][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int g2 = min(gg + q * kBRW, ge.g_last);
-              const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
-              const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
-                  a.partial + ((static_cast<size_t>(grp) * a.G + g2) * 2 + sgn) * slot_floats);
+          for (int bb = 0; bb < NB; ++bb)
 #pragma unroll
-              for (int k = 0; k < 4; ++k)
-                v[q][k] = __hip_atomic_load(p + bb * 256 + k * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int k = 0; k < 4; ++k)
+              v[bb][k] = __hip_atomic_load(p + bb * 64 + k * 16 + m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+          for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              acc[bb][2 * k] += __uint_as_float(static_cast<unsigned>(v[bb][k] & 0xFFFFFFFFull));
+              acc[bb][2 * k + 1] += __uint_as_float(static_cast<unsigned>(v[bb][k] >> 32));
             }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              if (gg + q * kBRW <= ge.g_last) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                  acc[bb][2 * k] += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
-                  acc[bb][2 * k + 1] += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
-                }
-              }
-            }
-          }
-          if (rw > 0) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) red[rw - 1][k][lane] = acc[bb][k];
-          }
-          __syncthreads();
-          if (rw == 0) {
-            for (int r = 0; r < kBRW - 1; ++r) {
-#pragma unroll
-              for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][k][lane];
-            }
-          }
-          __syncthreads();
         }
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            acc[bb][k] += __shfl_xor(acc[bb][k], 16, kWave);
+            acc[bb][k] += __shfl_xor(acc[bb][k], 32, kWave);
+          }
+        if (rw > 0 && kgrp == 0) {
+#pragma unroll
+          for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) red[rw - 1][bb][k][m] = acc[bb][k];
+        }
+        __syncthreads();
+        if (rw == 0 && kgrp == 0) {
+          for (int r = 0; r < kBRW - 1; ++r)
+#pragma unroll
+            for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+              for (int k = 0; k < 8; ++k) acc[bb][k] += red[r][bb][k][m];
+        }
+        __syncthreads();
       }
     }
     if (last) {   // uniform over the workgroup
       token_scales<T, kBRW>(a, b0, NB, scale_s, lane, rw);
       __syncthreads();
-      if (rw == 0 && colv) {
+      if (rw == 0 && kgrp == 0 && colv) {
 #pragma unroll
         for (int bb = 0; bb < NB; ++bb)
           if (b0 + bb < a.B) store_out8<T>(a, b0 + bb, col, acc[bb], scale_s[bb]);
@@ -509,10 +537,14 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
   }
 }
 
+}  // namespace
+bool batched_uses_mfma(int B, bool coef_scale);
+namespace {
+
 template <typename T>
 hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
   const dim3 block(kBThreads);
-  if (a.B <= 4 || a.coef_scale) {
+  if (!batched_uses_mfma(a.B, a.coef_scale != nullptr)) {
     // (a per-channel coefficient scale is applied in fp32, which only the FMA kernel does)
     if (a.B <= 2) {
       hipLaunchKernelGGL((skinny_fma_kernel<T, 2>), dim3(a.G, (a.B + 1) / 2), block, 0, st, a);
@@ -529,17 +561,16 @@ hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
 
 }  // namespace
 
-bool batched_uses_mfma(int B, bool coef_scale) { return B > 4 && !coef_scale; }
+bool batched_uses_mfma(int B, bool coef_scale) { return B >= 2 && !coef_scale; }
 
 int batched_tokens_per_group(int B, bool coef_scale) {
-  if (B <= 2) return 2;
-  if (!batched_uses_mfma(B, coef_scale)) return 4;
-  return B <= 16 ? 16 : 32;
+  if (batched_uses_mfma(B, coef_scale)) return B <= 16 ? 16 : 32;
+  return B <= 2 ? 2 : 4;
 }
 
 GemvPlan plan_batched(int d_in, int d_out, bool mfma) {
   GemvPlan p;
-  p.strip_cols = mfma ? kMStrip : kStripCols;
+  p.strip_cols = 128;   // both batched kernels work on 128-column strips
   p.nstrips = (d_out + p.strip_cols - 1) / p.strip_cols;
   const long T = static_cast<long>(p.nstrips) * d_in;
   long G = tuning().g_target > 0 ? tuning().g_target : 256;     // one workgroup per compute unit

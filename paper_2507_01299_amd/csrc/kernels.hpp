@@ -82,7 +82,7 @@ struct BatchArgs {
   const uint16_t* residual;
   uint16_t* y_pre;
 };
-constexpr int kBatchChunkMax = 1024;   // rows per workgroup segment (LDS coefficient staging)
+constexpr int kBatchChunkMax = 4096;   // rows per workgroup segment (LDS coefficient staging)
 GemvPlan plan_batched(int d_in, int d_out, bool mfma);
 bool batched_uses_mfma(int B, bool coef_scale);
 int batched_tokens_per_group(int B, bool coef_scale);

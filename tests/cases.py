@@ -41,7 +41,7 @@ def _dense_attention_half(X, W, shape, use_rms):
 
 def build_block_layer(shape: synth.LayerShape, p: float, seed: int, n_cal: int,
                       use_rms: bool = True, latent: str = "gauss", with_adapter: bool = False,
-                      Ks=None) -> LayerCase:
+                      Ks=None, with_rms_scale: bool = False, explicit_Q: bool = True) -> LayerCase:
     """One decoder layer with explicit per-block rotations Q_attn, Q_mlp (the block-level
     variant): q|k|v and gate|up are folded with Q^T on the input side; o and down see the
     unrotated h2, h4."""
@@ -74,10 +74,20 @@ def build_block_layer(shape: synth.LayerShape, p: float, seed: int, n_cal: int,
     if Ks is None:
         Ks = (O.kept_count(shape.d, p), O.kept_count(shape.d_q, p),
               O.kept_count(shape.d, p), O.kept_count(shape.d_ff, p))
+    g_attn = g_mlp = None
+    if with_rms_scale:       # learned pre-norm scales (any positive vector serves)
+        rs = np.random.Generator(np.random.PCG64(seed + 9))
+        bits["rms_attn"], va = _store(rs.uniform(0.5, 1.5, shape.d), dt)
+        bits["rms_mlp"], vm = _store(rs.uniform(0.5, 1.5, shape.d), dt)
+        g_attn, g_mlp = va.astype(np.float64), vm.astype(np.float64)
+    if not explicit_Q:       # x is taken to arrive in the block's basis already: no rotation kernels
+        bits["Q_attn"] = bits["Q_mlp"] = None
     layer = O.Layer(shape.d, shape.d_q, shape.d_kv, shape.d_ff, shape.head_dim, *Ks,
                     Wqkv=vals["Wqkv"], Wo=vals["Wo"], Wgu=vals["Wgu"], Wdown=vals["Wdown"],
-                    Q_attn=vals["Q_attn"].astype(np.float64), Q_mlp=vals["Q_mlp"].astype(np.float64),
+                    Q_attn=vals["Q_attn"].astype(np.float64) if explicit_Q else None,
+                    Q_mlp=vals["Q_mlp"].astype(np.float64) if explicit_Q else None,
                     adapter=None if A is None else vals["adapter"].astype(np.float64),
+                    rms_attn=g_attn, rms_mlp=g_mlp,
                     rms_eps=RMS_EPS if use_rms else -1.0, dtype=dt)
     dense = dict(W=W, Q_attn=Q_attn, Q_mlp=Q_mlp, Wqkv=Wqkv, Wgu=Wgu)
     return LayerCase(shape, bits, layer, dense, src)

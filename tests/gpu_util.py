@@ -34,7 +34,8 @@ def device_layer(case, device="cuda:0"):
                      Wqkv=to_dev(b["Wqkv"], dt, device), Wo=to_dev(b["Wo"], dt, device),
                      Wgu=to_dev(b["Wgu"], dt, device), Wdown=to_dev(b["Wdown"], dt, device), dtype=dt,
                      Q_attn=to_dev(b.get("Q_attn"), dt, device), Q_mlp=to_dev(b.get("Q_mlp"), dt, device),
-                     adapter=to_dev(b.get("adapter"), dt, device), rms_eps=L.rms_eps)
+                     adapter=to_dev(b.get("adapter"), dt, device), rms_attn=to_dev(b.get("rms_attn"), dt, device),
+                     rms_mlp=to_dev(b.get("rms_mlp"), dt, device), rms_eps=L.rms_eps)
 
 
 def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.Tensor, tol=REL_L2_TOL) -> dict:

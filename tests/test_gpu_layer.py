@@ -69,6 +69,19 @@ def test_ragged_layer_shapes(api, fused_mode):
         check_layer_trace(case.layer, xb, tr, out)
 
 
+@pytest.mark.parametrize("B", [1, 3, 6])
+@pytest.mark.parametrize("explicit_Q", [True, False])
+def test_learned_prenorm_scales_and_no_norm(api, fused_mode, B, explicit_Q):
+    """Pre-norm with a learned per-channel scale (applied in fp32 in front of the rotation, or inside
+    the fused prologue when there is no explicit rotation), and a layer with the pre-norm disabled."""
+    shape = synth.LayerShape("tiny", 256, 256, 64, 704, 32, "f16")
+    for use_rms, scale in ((True, True), (False, False)):
+        case = cases.build_block_layer(shape, 0.4, seed=81, n_cal=768, use_rms=use_rms, with_rms_scale=scale,
+                                       explicit_Q=explicit_Q, with_adapter=True)
+        xb, out, tr, dl, ws = _run_layer(api, case, B, seed=5)
+        check_layer_trace(case.layer, xb, tr, out)
+
+
 def test_folded_stack_tiny(api, fused_mode):
     """Deployed form: no explicit rotations, per-layer adapters, x carried in the layer basis."""
     shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "f16")
