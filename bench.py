@@ -44,6 +44,79 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def offline_report(args, api, torch, shape, cfg, dev):
+    """Matrix-core contractions of the offline part for one layer of the chosen shape: second
+    moment of n_cal tokens, the four folds of the deployed form and the residual adapter.  Times are
+    HIP-event averages; TFLOP/s counts 2 M N K once per product (the extra passes over the 16-bit
+    terms of an fp32 rotation are overhead, not work), against the dense 16-bit MFMA peak."""
+    td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
+    d, d_q, d_kv, d_ff, n = shape.d, shape.d_q, shape.d_kv, shape.d_ff, cfg["n_cal"]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1299)
+
+    def gauss(r, c, s=0.02):
+        return (torch.randn(r, c, generator=gen, device=dev, dtype=torch.float32) * s).to(td)
+
+    X = gauss(n, d, 1.0)
+    Q = torch.linalg.qr(torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32))[0].contiguous()
+    Q2 = torch.linalg.qr(torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32))[0].contiguous()
+    sc = api.OfflineScratch(d, shape.dtype)
+    C = torch.empty(d, d, dtype=torch.float32, device=dev)
+    Wqkv, Wgu, Wo, Wdown = gauss(d, d_q + 2 * d_kv), gauss(d, 2 * d_ff), gauss(d_q, d), gauss(d_ff, d)
+    outs = [torch.empty_like(w) for w in (Wqkv, Wgu, Wo, Wdown)]
+    A = torch.empty(d, d, dtype=td, device=dev)
+    jobs = [
+        ("second_moment", lambda: api.second_moment(X, C, shape.dtype), 2.0 * n * d * d, 2.0 * n * d * d / 2),
+        ("fold_input_qkv", lambda: api.fold_input(Q, Wqkv, outs[0], shape.dtype, sc), 2.0 * d * d * Wqkv.shape[1], None),
+        ("fold_input_gate_up", lambda: api.fold_input(Q, Wgu, outs[1], shape.dtype, sc), 2.0 * d * d * Wgu.shape[1], None),
+        ("fold_output_o", lambda: api.fold_output(Wo, Q, outs[2], shape.dtype, sc), 2.0 * d_q * d * d, None),
+        ("fold_output_down", lambda: api.fold_output(Wdown, Q, outs[3], shape.dtype, sc), 2.0 * d_ff * d * d, None),
+        ("residual_adapter", lambda: api.residual_adapter(Q, Q2, A, shape.dtype, sc), 2.0 * d * d * d, None),
+    ]
+    reps = max(3, min(args.steps, 20))
+    rows, total_ms = {}, 0.0
+    for name, fn, flops, _ in jobs:
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        rows[name] = dict(ms=round(ms, 4), TFLOPs=round(flops / (ms * 1e-3) / 1e12, 1))
+        total_ms += ms
+    # vendor BLAS on the same second moment, for context (16-bit inputs, 16-bit output)
+    for _ in range(2):
+        torch.matmul(X.T, X)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        torch.matmul(X.T, X)
+    e1.record()
+    torch.cuda.synchronize()
+    blas_ms = e0.elapsed_time(e1) / reps
+    dom = "fold_input_gate_up"
+    report = {
+        "metric": "offline_contractions_ms_per_layer", "value": round(total_ms, 3), "unit": "ms", "n_gpus": 1,
+        "steps": reps, "warmup": 2, "ms_per_step": round(total_ms, 3), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"offline contractions of one {shape.name} layer, {n} calibration tokens",
+                   "shape": shape.name},
+        "roofline": {"bound": "mfma", "achieved": rows[dom]["TFLOPs"], "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": round(rows[dom]["TFLOPs"] / 2500.0, 4), "traffic": None,
+                     "kernel": f"contraction_kernel ({dom}: Q^T W with Q in {2 if shape.dtype == 'f16' else 3} "
+                               "16-bit terms; flops counted once)"},
+        "cpu_baseline": None,
+        "extra": {"per_call": rows, "blas_XtX_16bit_ms": round(blas_ms, 4),
+                  "blas_XtX_TFLOPs": round(2.0 * n * d * d / (blas_ms * 1e-3) / 1e12, 1)},
+    }
+    print(json.dumps(report), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +134,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy kernel) so that hardware counters "
                          "read under rocprofv3 can be scaled by a transfer of known size")
+    ap.add_argument("--offline", action="store_true",
+                    help="time the offline contractions (second moment, folds, adapter) of the chosen "
+                         "config's layer instead of the decode step; prints its own JSON line")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="larosa_set_tuning(KEY, VALUE) before anything is sized (experiments)")
     args = ap.parse_args()
@@ -83,6 +159,8 @@ def main():
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
     shape = synth.SHAPES[cfg["shape"]]
+    if args.offline:
+        return offline_report(args, api, torch, shape, cfg, dev)
     td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
     p, B, nsets = args.sparsity, args.batch, max(1, args.nsets)
     d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff

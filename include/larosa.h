@@ -140,6 +140,42 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B);
 int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int B,
                          const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- Offline part on the GPU (Sec. 4.2: PCA rotation of each layer's input, rotation folded into the
+ * neighbouring weights, residual adapter between consecutive layers).  The eigendecomposition itself
+ * is left to the caller's solver: these calls produce its input and consume its output.
+ * All pointers are device memory; matrices are dense row-major; d, d_in, d_out are multiples of 8;
+ * 16-bit tensors are of type t; every call is asynchronous on `stream`.  Rotations are passed in fp32
+ * and are NOT rounded to 16 bits before the products: they are split into 16-bit terms in `ws`
+ * (borrowed for the duration of the call's kernels, 256-byte aligned).  Errors as for the calls above:
+ * LAROSA_EINVAL for null/misaligned pointers or bad sizes, LAROSA_EWORKSPACE for a workspace that is
+ * too small, LAROSA_EHIP when a launch fails. */
+
+/* Bytes of workspace the three folding calls below need for d x d rotations of type t (host only). */
+size_t larosa_offline_workspace_bytes(int d, larosa_dtype t);
+
+/* Second-moment accumulation (Sec. 4.2): C (+)= X^T X for n_tokens calibration rows X [n_tokens, d]
+ * (16-bit, type t), C [d, d] fp32, exactly symmetric.  accumulate = 0 overwrites C, 1 adds to it, so a
+ * calibration set can be fed in batches; the caller divides by the token count if it wants the
+ * average (the eigenvectors do not depend on it).  fp32 accumulation on the matrix cores. */
+int larosa_second_moment(const void* X, int n_tokens, int d, larosa_dtype t, float* C, int accumulate,
+                         void* stream);
+
+/* Input-side fold (Sec. 4.2, Eq. 9-10): W_out = Q^T W for W [d, d_out] in the input-channel-major layout
+ * the projections read, Q [d, d] fp32 with the principal directions as columns.  W_out [d, d_out] is
+ * rounded once to type t.  W_out must not alias W. */
+int larosa_fold_input(const float* Q, const void* W, int d, int d_out, larosa_dtype t, void* W_out, void* ws,
+                      size_t ws_bytes, void* stream);
+
+/* Output-side fold (Sec. 3.2): W_out = W Q for W [d_in, d]: the projection then emits its output in the
+ * basis Q.  W_out [d_in, d], rounded once to type t, must not alias W. */
+int larosa_fold_output(const void* W, const float* Q, int d_in, int d, larosa_dtype t, void* W_out, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/* Residual adapter (Sec. 4.2): A = Q_l^T Q_next, [d, d], rounded once to type t: the dense mat-vec that
+ * takes the residual stream from layer l's basis to the next layer's. */
+int larosa_residual_adapter(const float* Q_l, const float* Q_next, int d, larosa_dtype t, void* A_out, void* ws,
+                            size_t ws_bytes, void* stream);
+
 /* Kernel launch tuning for experiments (host state, not thread-safe; set it before sizing a
  * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
  * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,

@@ -69,6 +69,12 @@ def lib() -> ctypes.CDLL:
         L.larosa_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Layer), i]
         L.larosa_layer_forward.argtypes = [ctypes.POINTER(_Layer), vp, vp, i, ctypes.POINTER(_Trace), vp, sz, vp]
         L.larosa_set_tuning.argtypes = [i, i]
+        L.larosa_offline_workspace_bytes.restype = sz
+        L.larosa_offline_workspace_bytes.argtypes = [i, i]
+        L.larosa_second_moment.argtypes = [vp, i, i, i, vp, i, vp]
+        L.larosa_fold_input.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.larosa_fold_output.argtypes = [vp, vp, i, i, i, vp, vp, sz, vp]
+        L.larosa_residual_adapter.argtypes = [vp, vp, i, i, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -159,6 +165,48 @@ def sparse_gemv(Wp, h, idx, y, dtype, ws: Workspace):
     _check(lib().larosa_sparse_gemv(_ptr(Wp), _ptr(h), _ptr(idx), _ptr(y), B, d_in, d_out, K, dtype_code(dtype),
                                     ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_sparse_gemv")
     return y
+
+
+class OfflineScratch:
+    """Device scratch for the folding calls (16-bit terms of the fp32 rotations)."""
+
+    def __init__(self, d: int, dtype, device="cuda:0"):
+        self.nbytes = int(lib().larosa_offline_workspace_bytes(d, dtype_code(dtype)))
+        self.buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
+        self.ptr = self.buf.data_ptr() + (-self.buf.data_ptr()) % 256
+
+
+def second_moment(X, C, dtype, accumulate: bool = False):
+    """C [d,d] fp32 (+)= X^T X for X [n,d] 16-bit."""
+    n, d = X.shape
+    _check(lib().larosa_second_moment(_ptr(X), n, d, dtype_code(dtype), _ptr(C), int(accumulate), _stream()),
+           "larosa_second_moment")
+    return C
+
+
+def fold_input(Q, W, W_out, dtype, scratch: OfflineScratch):
+    """W_out [d,d_out] = Q^T W with Q [d,d] fp32."""
+    d, d_out = W.shape
+    _check(lib().larosa_fold_input(_ptr(Q), _ptr(W), d, d_out, dtype_code(dtype), _ptr(W_out),
+                                   ctypes.c_void_p(scratch.ptr), scratch.nbytes, _stream()), "larosa_fold_input")
+    return W_out
+
+
+def fold_output(W, Q, W_out, dtype, scratch: OfflineScratch):
+    """W_out [d_in,d] = W Q with Q [d,d] fp32."""
+    d_in, d = W.shape
+    _check(lib().larosa_fold_output(_ptr(W), _ptr(Q), d_in, d, dtype_code(dtype), _ptr(W_out),
+                                    ctypes.c_void_p(scratch.ptr), scratch.nbytes, _stream()), "larosa_fold_output")
+    return W_out
+
+
+def residual_adapter(Q_l, Q_next, A_out, dtype, scratch: OfflineScratch):
+    """A_out [d,d] = Q_l^T Q_next, both fp32."""
+    d = Q_l.shape[0]
+    _check(lib().larosa_residual_adapter(_ptr(Q_l), _ptr(Q_next), d, dtype_code(dtype), _ptr(A_out),
+                                         ctypes.c_void_p(scratch.ptr), scratch.nbytes, _stream()),
+           "larosa_residual_adapter")
+    return A_out
 
 
 class Layer:

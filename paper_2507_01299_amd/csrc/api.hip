@@ -486,6 +486,120 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   return LAROSA_OK;
 }
 
+// ---- offline contractions -------------------------------------------------------------------
+
+namespace {
+
+// f16 terms of a rotation are taken from 64 Q: entries of an orthogonal matrix are at most 1 in
+// magnitude and mostly near 1/sqrt(d), whose second term would fall into the f16 subnormals.
+inline float term_pre_scale(bool bf16) { return bf16 ? 1.0f : 64.0f; }
+
+inline size_t terms_bytes(int d, bool bf16) {
+  return round_up(static_cast<size_t>(contraction_terms(bf16)) * d * d * 2, 256);
+}
+
+int check_offline(const void* a, const void* b, const void* c, int d, larosa_dtype t) {
+  if (!a || !b || !c || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return LAROSA_EINVAL;
+  if (d < 8 || d % 8 || d > 32768) return LAROSA_EINVAL;
+  return LAROSA_OK;
+}
+
+}  // namespace
+
+size_t larosa_offline_workspace_bytes(int d, larosa_dtype t) {
+  if (d < 8 || !dtype_ok(t)) return 0;
+  return 2 * terms_bytes(d, t == LAROSA_BF16);
+}
+
+int larosa_second_moment(const void* X, int n_tokens, int d, larosa_dtype t, float* C, int accumulate,
+                         void* stream) {
+  if (int rc = check_offline(X, X, C, d, t)) return rc;
+  if (n_tokens < 1) return LAROSA_EINVAL;
+  ContractionArgs a{};
+  a.A = a.B = static_cast<const uint16_t*>(X);
+  a.M = a.N = d; a.Kd = n_tokens;
+  a.npairs = 1;
+  a.C32 = C;
+  a.post_scale = 1.0f;
+  a.accumulate = accumulate ? 1 : 0;
+  a.symmetric = 1;
+  return launch_contraction(a, true, t == LAROSA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess ? LAROSA_OK
+                                                                                                       : LAROSA_EHIP;
+}
+
+int larosa_fold_input(const float* Q, const void* W, int d, int d_out, larosa_dtype t, void* W_out, void* ws,
+                      size_t ws_bytes, void* stream) {
+  if (int rc = check_offline(Q, W, W_out, d, t)) return rc;
+  if (d_out < 8 || d_out % 8 || W == W_out) return LAROSA_EINVAL;
+  const bool bf16 = t == LAROSA_BF16;
+  if (!ws || !aligned(ws, 256) || ws_bytes < terms_bytes(d, bf16)) return LAROSA_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* terms = static_cast<uint16_t*>(ws);
+  const long n = static_cast<long>(d) * d;
+  if (launch_split_terms(Q, terms, n, term_pre_scale(bf16), bf16, st) != hipSuccess) return LAROSA_EHIP;
+  ContractionArgs a{};
+  a.A = terms; a.B = static_cast<const uint16_t*>(W);
+  a.M = d; a.N = d_out; a.Kd = d;
+  a.a_term_stride = n;
+  a.npairs = contraction_terms(bf16);
+  for (int i = 0; i < a.npairs; ++i) { a.pa[i] = i; a.pb[i] = 0; }
+  a.C16 = static_cast<uint16_t*>(W_out);
+  a.post_scale = 1.0f / term_pre_scale(bf16);
+  return launch_contraction(a, true, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
+int larosa_fold_output(const void* W, const float* Q, int d_in, int d, larosa_dtype t, void* W_out, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (int rc = check_offline(Q, W, W_out, d, t)) return rc;
+  if (d_in < 8 || d_in % 8 || W == W_out) return LAROSA_EINVAL;
+  const bool bf16 = t == LAROSA_BF16;
+  if (!ws || !aligned(ws, 256) || ws_bytes < terms_bytes(d, bf16)) return LAROSA_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* terms = static_cast<uint16_t*>(ws);
+  const long n = static_cast<long>(d) * d;
+  if (launch_split_terms(Q, terms, n, term_pre_scale(bf16), bf16, st) != hipSuccess) return LAROSA_EHIP;
+  ContractionArgs a{};
+  a.A = static_cast<const uint16_t*>(W); a.B = terms;
+  a.M = d_in; a.N = d; a.Kd = d;
+  a.b_term_stride = n;
+  a.npairs = contraction_terms(bf16);
+  for (int i = 0; i < a.npairs; ++i) { a.pa[i] = 0; a.pb[i] = i; }
+  a.C16 = static_cast<uint16_t*>(W_out);
+  a.post_scale = 1.0f / term_pre_scale(bf16);
+  return launch_contraction(a, false, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
+int larosa_residual_adapter(const float* Q_l, const float* Q_next, int d, larosa_dtype t, void* A_out, void* ws,
+                            size_t ws_bytes, void* stream) {
+  if (int rc = check_offline(Q_l, Q_next, A_out, d, t)) return rc;
+  const bool bf16 = t == LAROSA_BF16;
+  const size_t tb = terms_bytes(d, bf16);
+  if (!ws || !aligned(ws, 256) || ws_bytes < 2 * tb) return LAROSA_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* ta = static_cast<uint16_t*>(ws);
+  uint16_t* tb16 = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + tb);
+  const long n = static_cast<long>(d) * d;
+  const float pre = term_pre_scale(bf16);
+  if (launch_split_terms(Q_l, ta, n, pre, bf16, st) != hipSuccess) return LAROSA_EHIP;
+  if (launch_split_terms(Q_next, tb16, n, pre, bf16, st) != hipSuccess) return LAROSA_EHIP;
+  ContractionArgs a{};
+  a.A = ta; a.B = tb16;
+  a.M = a.N = a.Kd = d;
+  a.a_term_stride = a.b_term_stride = n;
+  // every product of terms whose combined weight is above the fp32 rounding of the full product
+  static const int f16_pairs[3][2] = {{0, 0}, {0, 1}, {1, 0}};
+  static const int bf16_pairs[6][2] = {{0, 0}, {0, 1}, {1, 0}, {1, 1}, {0, 2}, {2, 0}};
+  a.npairs = bf16 ? 6 : 3;
+  for (int i = 0; i < a.npairs; ++i) {
+    a.pa[i] = bf16 ? bf16_pairs[i][0] : f16_pairs[i][0];
+    a.pb[i] = bf16 ? bf16_pairs[i][1] : f16_pairs[i][1];
+  }
+  a.C16 = static_cast<uint16_t*>(A_out);
+  a.post_scale = 1.0f / (pre * pre);
+  return launch_contraction(a, true, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
 int larosa_set_tuning(int key, int value) {
   switch (key) {
     case 0:

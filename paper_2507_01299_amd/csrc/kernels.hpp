@@ -106,4 +106,26 @@ hipError_t launch_rmsnorm(const uint16_t* x, const uint16_t* scale, uint16_t* y,
 hipError_t launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t s);
 hipError_t launch_copy_u16(const uint16_t* src, uint16_t* dst, size_t n, hipStream_t s);
 
+// ---- offline contractions on the matrix cores (offline.hip): C[m,n] = post_scale * sum over the listed
+// term pairs and over k of A_term(k,m) * B_term(k,n), fp32 accumulate.
+struct ContractionArgs {
+  const uint16_t* A;        // a_kmajor: [terms][Kd][M], else [terms][M][Kd]
+  const uint16_t* B;        // [terms][Kd][N]
+  int M, N, Kd;
+  long a_term_stride, b_term_stride;   // elements between the 16-bit terms of a split operand
+  int npairs;
+  int pa[8], pb[8];         // term indices of each product that is added up
+  float* C32;               // [M][N] fp32, or null
+  uint16_t* C16;            // [M][N] rounded to the storage type, or null
+  float post_scale;
+  int accumulate;           // C32 only: add to what is there
+  int symmetric;            // A == B, M == N: compute tiles on or above the diagonal, store both halves
+  int tiles_m, tiles_n, patches_m, patches_n;   // filled in by launch_contraction
+};
+hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s);
+// number of 16-bit terms an fp32 operand is split into (2 for f16, 3 for bf16)
+int contraction_terms(bool bf16);
+// dst[t][i] for t < terms: src[i] * pre_scale = sum_t dst[t][i] up to the last term's rounding
+hipError_t launch_split_terms(const float* src, uint16_t* dst, long n, float pre_scale, bool bf16, hipStream_t s);
+
 }  // namespace larosa

@@ -1,0 +1,212 @@
+"""GPU parity of the offline contractions (second moment, folds, residual adapter) through the
+C ABI against the fp64 oracle on the same seeded inputs.
+
+Tolerances.  The second moment is accumulated in fp32 from exact products of 16-bit inputs, so
+|C_gpu - C_oracle|_ij <= tol * sqrt(C_ii C_jj) (Cauchy-Schwarz scale of the entry) with
+tol = 5e-5 (about sqrt(n) * 2^-24 is expected, n * 2^-24 is the worst case for n <= 4096).
+Folded weights and adapters are stored 16-bit tensors: they must agree with the oracle's single
+rounding of the fp64 product within one unit in the last place everywhere, with at most 2 % of the
+entries off by that unit (fp32 accumulation can flip a rounding that sits near a tie), and within
+the 2e-3 relative L2 stated for 16-bit outputs.  An entry that is itself far smaller than its terms
+(cancellation; bf16 keeps 8 bits down to 1e-38, so its unit shrinks with the entry) is held to the
+fp32 accumulation bound instead: 2^-21 |a_i| |b_j|, the Cauchy-Schwarz scale of the sum.
+The eigendecomposition is not a GPU kernel here: every test hands the same fp32 rotation to both
+sides."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import larosa_oracle as O
+from paper_2507_01299_amd import synth
+from tests import cases
+from tests.gpu_util import REL_L2_TOL, rel_l2, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+SM_TOL = 5e-5
+ULP_FRACTION = 0.02
+
+
+@pytest.fixture(scope="module")
+def api(gpu_device):
+    from paper_2507_01299_amd import api as A
+    A.lib()
+    return A
+
+
+def _ordered(bits: np.ndarray) -> np.ndarray:
+    """16-bit sign-magnitude patterns -> integers in value order (one step = one ulp)."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+def _check_stored(got_bits, want64, dtype, what, scale):
+    """scale: |a_i| |b_j| per entry (array or scalar)."""
+    want_bits = O.encode16(want64, dtype)
+    step = np.abs(_ordered(got_bits) - _ordered(want_bits))
+    err = np.abs(O.decode16(got_bits, dtype) - O.decode16(want_bits, dtype))
+    bad = (step > 1) & (err > 2.0 ** -21 * scale)
+    assert not bad.any(), f"{what}: {int(bad.sum())} entries beyond 1 ulp, worst {int(step[bad].max())} ulp / {err[bad].max():.3e}"
+    step = np.minimum(step, 1)
+    frac = float((step != 0).mean())
+    assert frac <= ULP_FRACTION, f"{what}: {frac:.4f} of the entries are one ulp off"
+    e = rel_l2(O.decode16(got_bits, dtype), O.decode16(want_bits, dtype))
+    assert e <= REL_L2_TOL
+    return frac, e
+
+
+def _calibration(n, d, seed, dtype):
+    src = synth.activation_source(d, seed)
+    bits = O.encode16(src.draw(n, seed + 1), dtype)
+    return bits, O.decode16(bits, dtype)
+
+
+def _rotation32(d, seed):
+    """An orthogonal matrix as an eigen-solver would return it, rounded to fp32."""
+    return synth.planted_basis(d, seed).astype(np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("n,d", [(100, 256), (777, 520), (33, 8), (1024, 1160)])
+def test_second_moment_matches_oracle(api, dtype, n, d):
+    print(f"second_moment dtype={dtype} n={n} d={d}", flush=True)
+    xb, x = _calibration(n, d, 7 + d, dtype)
+    C = torch.full((d, d), 7.0, dtype=torch.float32, device="cuda:0")
+    api.second_moment(to_dev(xb, dtype), C, dtype)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy().astype(np.float64)
+    want = O.second_moment(x) * n
+    scale = np.sqrt(np.outer(np.diag(want), np.diag(want)))
+    assert np.all(np.abs(got - want) <= SM_TOL * scale + 1e-30)
+    assert np.array_equal(got, got.T)                       # mirrored stores: exactly symmetric
+    # two batches accumulated == one pass (same tolerance), and accumulate=0 overwrote the 7s
+    h = n // 2 if n > 1 else 1
+    C2 = torch.empty_like(C)
+    api.second_moment(to_dev(xb[:h], dtype), C2, dtype)
+    api.second_moment(to_dev(xb[h:], dtype), C2, dtype, accumulate=True)
+    torch.cuda.synchronize()
+    got2 = C2.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got2 - want) <= SM_TOL * scale + 1e-30)
+    assert np.array_equal(got2, got2.T)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d,d_out", [(256, 704), (520, 136), (8, 8), (384, 1408)])
+def test_fold_input_matches_oracle(api, dtype, d, d_out):
+    print(f"fold_input dtype={dtype} d={d} d_out={d_out}", flush=True)
+    Q = _rotation32(d, 3 + d)
+    wb = O.encode16(synth.gaussian_weight(d, d_out, 11 + d), dtype)
+    out = torch.zeros(d, d_out, dtype=api.torch_dtype(dtype), device="cuda:0")
+    sc = api.OfflineScratch(d, dtype)
+    api.fold_input(torch.from_numpy(Q).cuda(), to_dev(wb, dtype), out, dtype, sc)
+    torch.cuda.synchronize()
+    want = O.fold_input_side(Q.astype(np.float64), O.decode16(wb, dtype))
+    wn = np.linalg.norm(O.decode16(wb, dtype), axis=0)
+    _check_stored(to_bits(out), want, dtype, "Q^T W", wn[None, :])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d_in,d", [(704, 256), (136, 520), (8, 8), (1000, 384)])
+def test_fold_output_matches_oracle(api, dtype, d_in, d):
+    print(f"fold_output dtype={dtype} d_in={d_in} d={d}", flush=True)
+    Q = _rotation32(d, 5 + d)
+    wb = O.encode16(synth.gaussian_weight(d_in, d, 13 + d), dtype)
+    out = torch.zeros(d_in, d, dtype=api.torch_dtype(dtype), device="cuda:0")
+    sc = api.OfflineScratch(d, dtype)
+    api.fold_output(to_dev(wb, dtype), torch.from_numpy(Q).cuda(), out, dtype, sc)
+    torch.cuda.synchronize()
+    want = O.fold_output_side(O.decode16(wb, dtype), Q.astype(np.float64))
+    wn = np.linalg.norm(O.decode16(wb, dtype), axis=1)
+    _check_stored(to_bits(out), want, dtype, "W Q", wn[:, None])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d", [256, 520, 8])
+def test_residual_adapter_matches_oracle(api, dtype, d):
+    print(f"residual_adapter dtype={dtype} d={d}", flush=True)
+    Ql, Qn = _rotation32(d, 17 + d), _rotation32(d, 19 + d)
+    out = torch.zeros(d, d, dtype=api.torch_dtype(dtype), device="cuda:0")
+    sc = api.OfflineScratch(d, dtype)
+    api.residual_adapter(torch.from_numpy(Ql).cuda(), torch.from_numpy(Qn).cuda(), out, dtype, sc)
+    torch.cuda.synchronize()
+    want = O.residual_adapter(Ql.astype(np.float64), Qn.astype(np.float64))
+    _check_stored(to_bits(out), want, dtype, "Q_l^T Q_next", 1.0)
+    # the adapter of a basis with itself is the identity up to the fp32 rounding of Q
+    api.residual_adapter(torch.from_numpy(Ql).cuda(), torch.from_numpy(Ql).cuda(), out, dtype, sc)
+    torch.cuda.synchronize()
+    eye = O.decode16(to_bits(out), dtype)
+    assert np.abs(eye - np.eye(d)).max() <= 1e-5
+
+
+def test_full_size_llama2_7b_on_sampled_columns(api):
+    """The launch configuration of the 7B-shaped layer (d = 4096, 4096 calibration tokens, q|k|v and
+    gate|up widths) checked on 48 sampled output columns the oracle computes one by one."""
+    dtype, d, n = "f16", 4096, 4096
+    print("offline full size d=4096", flush=True)
+    rng = np.random.default_rng(4242)
+    xb, x = _calibration(n, d, 99, dtype)
+    C = torch.empty(d, d, dtype=torch.float32, device="cuda:0")
+    api.second_moment(to_dev(xb, dtype), C, dtype)
+    torch.cuda.synchronize()
+    cols = np.sort(rng.choice(d, 48, replace=False))
+    got = C[:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+    diag = np.einsum("ij,ij->j", x, x)
+    want = x.T @ x[:, cols]
+    assert np.all(np.abs(got - want) <= SM_TOL * np.sqrt(np.outer(diag, diag[cols])))
+    assert torch.equal(C, C.T)
+    del C
+    Q = _rotation32(d, 77)
+    Q64 = Q.astype(np.float64)
+    Qd = torch.from_numpy(Q).cuda()
+    sc = api.OfflineScratch(d, dtype)
+    for d_out, seed in ((12288, 1), (22016, 2)):
+        wb = O.encode16(synth.gaussian_weight(d, d_out, seed), dtype)
+        out = torch.zeros(d, d_out, dtype=torch.float16, device="cuda:0")
+        api.fold_input(Qd, to_dev(wb, dtype), out, dtype, sc)
+        torch.cuda.synchronize()
+        cols = np.sort(rng.choice(d_out, 48, replace=False))
+        got_bits = to_bits(out[:, torch.from_numpy(cols).cuda()].contiguous())
+        want = O.fold_input_side(Q64, O.decode16(wb[:, cols], dtype))
+        wn = np.linalg.norm(O.decode16(wb[:, cols], dtype), axis=0)
+        _check_stored(got_bits, want, dtype, f"Q^T W, d_out={d_out}", wn[None, :])
+        del out
+    wb = O.encode16(synth.gaussian_weight(11008, d, 3), dtype)
+    out = torch.zeros(11008, d, dtype=torch.float16, device="cuda:0")
+    api.fold_output(to_dev(wb, dtype), Qd, out, dtype, sc)
+    torch.cuda.synchronize()
+    rows = np.sort(rng.choice(11008, 48, replace=False))
+    got_bits = to_bits(out[torch.from_numpy(rows).cuda()].contiguous())
+    wn = np.linalg.norm(O.decode16(wb[rows], dtype), axis=1)
+    _check_stored(got_bits, O.fold_output_side(O.decode16(wb[rows], dtype), Q64), dtype, "W Q", wn[:, None])
+
+
+def test_gpu_prepared_layer_keeps_the_dense_output_at_full_K(api):
+    """Computational invariance through the GPU pipeline: rotations from the GPU second moment (fp64
+    eigen-solver on the host in between), weights folded on the GPU, then the decode layer with
+    K = d equals the unrotated dense layer (Sec. 3.2).  16-bit storage of weights and stage outputs
+    bounds the agreement, not the method."""
+    from paper_2507_01299_amd import offline
+    shape = synth.LayerShape("tiny", 256, 256, 64, 704, 32, "f16")
+    dtype = shape.dtype
+    seed = 555
+    src = synth.activation_source(shape.d, seed)
+    W = synth.layer_weights(shape, seed + 100)
+    wb = {k: O.encode16(v, dtype) for k, v in W.items()}
+    Wd = {k: O.decode16(v, dtype) for k, v in wb.items()}          # the dense model IS the stored weights
+    Xc_bits = O.encode16(src.draw(1024, seed + 1), dtype)
+    dev = {k: to_dev(v, dtype) for k, v in wb.items()}
+    ops = offline.prepare_block_layer(shape, dev, to_dev(Xc_bits, dtype), rms_eps=cases.RMS_EPS)
+    L = api.Layer(shape.d, shape.d_q, shape.d_kv, shape.d_ff, shape.head_dim, shape.d, shape.d_q, shape.d,
+                  shape.d_ff, ops["Wqkv"], ops["Wo"], ops["Wgu"], ops["Wdown"], dtype, Q_attn=ops["Q_attn"],
+                  Q_mlp=ops["Q_mlp"], rms_eps=cases.RMS_EPS)
+    B = 3
+    xb = O.encode16(src.draw(B, seed + 5), dtype)
+    x = to_dev(xb, dtype)
+    out = torch.zeros_like(x)
+    ws = api.Workspace(L.workspace_bytes(B))
+    api.layer_forward(L, x, out, ws)
+    torch.cuda.synchronize()
+    want = cases.dense_layer_reference(Wd, shape, O.decode16(xb, dtype))
+    got = O.decode16(to_bits(out), dtype)
+    for b in range(B):
+        assert rel_l2(got[b], want[b]) <= 3e-3

@@ -82,3 +82,25 @@ def test_layer_struct_validation(lib):
     fake = ctypes.c_void_p(0x1000)
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, fake, 1, None, fake, n, None) == api.EINVAL  # x_out aliases x
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, ctypes.c_void_p(0x2000), 1, None, fake, 16, None) == api.EWORKSPACE
+
+
+def test_offline_calls_reject_invalid_arguments(lib):
+    from paper_2507_01299_amd import api
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    big = 1 << 30
+    assert lib.larosa_offline_workspace_bytes(4096, 0) == 2 * 2 * 4096 * 4096 * 2
+    assert lib.larosa_offline_workspace_bytes(4096, 1) == 2 * 3 * 4096 * 4096 * 2
+    assert lib.larosa_offline_workspace_bytes(4096, 5) == 0
+    assert lib.larosa_second_moment(None, 16, 64, 0, fake, 0, None) == api.EINVAL
+    assert lib.larosa_second_moment(fake, 0, 64, 0, fake, 0, None) == api.EINVAL
+    assert lib.larosa_second_moment(fake, 16, 60, 0, fake, 0, None) == api.EINVAL
+    assert lib.larosa_second_moment(odd, 16, 64, 0, fake, 0, None) == api.EINVAL
+    assert lib.larosa_fold_input(fake, fake, 64, 64, 0, fake, fake, big, None) == api.EINVAL      # aliasing
+    assert lib.larosa_fold_input(fake, fake, 64, 60, 0, odd, fake, big, None) == api.EINVAL
+    other = ctypes.c_void_p(0x2000)
+    assert lib.larosa_fold_input(fake, fake, 64, 64, 0, other, fake, 16, None) == api.EWORKSPACE
+    assert lib.larosa_fold_output(fake, fake, 64, 64, 0, other, None, big, None) == api.EWORKSPACE
+    assert lib.larosa_fold_output(fake, fake, 12, 64, 0, other, fake, big, None) == api.EINVAL
+    assert lib.larosa_residual_adapter(fake, fake, 64, 2, other, fake, big, None) == api.EINVAL
+    assert lib.larosa_residual_adapter(fake, fake, 64, 1, other, fake, 3 * 64 * 64 * 2, None) == api.EWORKSPACE
