@@ -9,7 +9,8 @@ Every function cites the passage of the paper (arXiv 2507.01299) it follows.
 16-bit tensors are carried as numpy uint16 bit patterns plus a dtype tag
 ("f16" | "bf16"); all arithmetic is fp64.
 
-Pinned by tests/test_oracle_*.py against closed forms, invariants, brute force
+Pinned by tests/test_oracle_*.py (4-bit weights and the threshold sparsifier in
+tests/test_oracle_w4_threshold.py) against closed forms, invariants, brute force
 on tiny inputs and the values the paper prints (tests/golden/).  Unpinned:
 nothing in this file.  (The paper's accuracy tables need real model weights
 and datasets and are outside what this oracle states: parity unpinned there.)
@@ -198,6 +199,84 @@ def sparse_project_masked(h: np.ndarray, idx: np.ndarray, Wp: np.ndarray) -> np.
 def sparse_project_batch(h: np.ndarray, idx: np.ndarray, Wp64: np.ndarray) -> np.ndarray:
     """Per-token index sets: y[b] = sum_t h[b, idx[b,t]] W'[idx[b,t], :]."""
     return np.stack([sparse_project_gather(h[b], idx[b], Wp64) for b in range(h.shape[0])])
+
+
+# --------------------------------------------------------------------------
+# 4-bit weights (W4A16, Sec. 5.4 / Table 9 use round-to-nearest codes; the paper
+# fixes no storage format: groups of 128 output columns per input-channel row and
+# the nibble order are this build's choice)
+# --------------------------------------------------------------------------
+
+W4_GROUP = 128
+
+
+def quantize_rtn_w4(W: np.ndarray, dtype: str, group: int = W4_GROUP):
+    """Symmetric round-to-nearest 4-bit codes of W [d_in, d_out], one scale per row and per
+    group of `group` consecutive output columns: s = max|w| / 7 stored in 16 bits,
+    q = clip(rint(w / s), -8, 7) + 8 in [0, 15] (q = 8 where s = 0).
+    Returns (codes uint8 [d_in, d_out], scale bit patterns uint16 [d_in, ceil(d_out/group)])."""
+    W = np.asarray(W, np.float64)
+    d_in, d_out = W.shape
+    ng = -(-d_out // group)
+    codes = np.empty((d_in, d_out), np.uint8)
+    sbits = np.empty((d_in, ng), np.uint16)
+    for g in range(ng):
+        blk = W[:, g * group:(g + 1) * group]
+        sb = encode16(np.abs(blk).max(axis=1) / 7.0, dtype)
+        s = decode16(sb, dtype)
+        q = np.zeros_like(blk)
+        nz = s > 0
+        q[nz] = np.rint(blk[nz] / s[nz, None])
+        codes[:, g * group:(g + 1) * group] = (np.clip(q, -8, 7) + 8).astype(np.uint8)
+        sbits[:, g] = sb
+    return codes, sbits
+
+
+def dequantize_w4(codes: np.ndarray, sbits: np.ndarray, dtype: str, group: int = W4_GROUP) -> np.ndarray:
+    """w = (q - 8) * s of the column's group, fp64."""
+    s = decode16(sbits, dtype)
+    cols = np.arange(codes.shape[1]) // group
+    return (codes.astype(np.float64) - 8.0) * s[:, cols]
+
+
+def pack_w4(codes: np.ndarray) -> np.ndarray:
+    """Eight codes per little-endian dword: nibble k (bits 4k..4k+3) of dword m of a row is the
+    code of column 8m + k.  [d_in, d_out] -> uint32 [d_in, d_out/8]."""
+    c = np.asarray(codes, np.uint32).reshape(codes.shape[0], -1, 8)
+    out = np.zeros(c.shape[:2], np.uint32)
+    for k in range(8):
+        out |= c[:, :, k] << np.uint32(4 * k)
+    return out
+
+
+def unpack_w4(packed: np.ndarray) -> np.ndarray:
+    p = np.asarray(packed, np.uint32)
+    return np.stack([(p >> np.uint32(4 * k)) & np.uint32(15) for k in range(8)], axis=-1).reshape(
+        p.shape[0], -1).astype(np.uint8)
+
+
+def sparse_project_w4(h: np.ndarray, idx: np.ndarray, codes: np.ndarray, sbits: np.ndarray, dtype: str) -> np.ndarray:
+    """Eq. 10 over the dequantised 4-bit weight: y_o = sum_t h[idx_t] (q[idx_t,o] - 8) s[idx_t, g(o)]."""
+    return np.asarray(h, np.float64)[idx] @ dequantize_w4(codes[idx], sbits[idx], dtype)
+
+
+# --------------------------------------------------------------------------
+# Magnitude-threshold sparsifier S_eps (Eq. 4-5): the comparison method whose kept
+# count varies from token to token (Sec. 4.1)
+# --------------------------------------------------------------------------
+
+
+def calibrate_threshold(H: np.ndarray, p: float) -> float:
+    """Cutoff from the empirical distribution of |h| over calibration entries (Eq. 4): the
+    smallest observed magnitude eps with  #(|h| <= eps) >= p * N."""
+    a = np.sort(np.abs(np.asarray(H, np.float64)).ravel())
+    k = int(np.ceil(p * a.size))
+    return float(a[k - 1]) if k >= 1 else 0.0
+
+
+def threshold_indices(h: np.ndarray, eps: float) -> np.ndarray:
+    """Kept channels of S_eps (Eq. 5): those with |h_i| > eps, ascending.  One token."""
+    return np.flatnonzero(np.abs(np.asarray(h, np.float64)) > eps).astype(np.int32)
 
 
 def silu(g: np.ndarray) -> np.ndarray:
