@@ -176,6 +176,35 @@ int larosa_fold_output(const void* W, const float* Q, int d_in, int d, larosa_dt
 int larosa_residual_adapter(const float* Q_l, const float* Q_next, int d, larosa_dtype t, void* A_out, void* ws,
                             size_t ws_bytes, void* stream);
 
+/* ---- 4-bit weights (W4A16).  The paper reports that the method keeps its accuracy on round-to-nearest
+ * and calibrated 4-bit weights (Sec. 5.4, Table 9) and names a kernel that does both as future work;
+ * it fixes no storage format, so the one here is this library's own:
+ *   Wq     [d_in, d_out/8] uint32: nibble k (bits 4k..4k+3) of dword m of row j = code q of column 8m+k
+ *   scales [d_in, ceil(d_out/128)] 16-bit (type t): weight(j, o) = (q - 8) * scales[j, o/128]
+ * i.e. symmetric codes with one scale per input-channel row and per group of 128 output columns, so
+ * that a kept row is still one contiguous burst and its scales fold into the row's coefficient. */
+
+/* Round-to-nearest quantisation of W [d_in, d_out] (16-bit, type t): scale = max|w| over the group / 7
+ * rounded to type t, q = clip(rint(w / scale), -8, 7) + 8 (q = 8 where the scale is 0).
+ * d_out % 8 == 0.  Device pointers, 16-byte aligned; asynchronous on `stream`. */
+int larosa_quantize_w4(const void* W, int d_in, int d_out, larosa_dtype t, void* Wq, void* scales, void* stream);
+
+/* Column-sparse projection (Sec. 4.3, Eq. 10) over the 4-bit weight:
+ *   y[b,o] = sum_t h[b, idx[b,t]] * (q[idx[b,t], o] - 8) * scales[idx[b,t], o/128],  fp32 accumulate,
+ * one rounding to type t.  idx as for larosa_sparse_gemv (ascending, distinct, per token), or NULL
+ * with K == d_in for the dense product over all rows.  Workspace as for larosa_sparse_gemv. */
+int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, const int32_t* idx, void* y, int B,
+                          int d_in, int d_out, int K, larosa_dtype t, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Magnitude-threshold sparsifier S_eps (Eq. 4-5), the comparison method of Sec. 4.1 whose kept count
+ * depends on the token: idx[b*d .. b*d + count[b]) = ascending channels with |h[b,i]| > eps (compared
+ * exactly: 16-bit magnitudes widened to fp32 against the fp32 eps; NaN is dropped).
+ * h [B, d] 16-bit, idx [B, d] int32 (capacity d per token), count [B] int32; device pointers;
+ * d % 8 == 0, d <= 32768.  Feeding a token's idx and count[b] (read back by the caller) to
+ * larosa_sparse_gemv gives the variable-K projection that the fixed-K Top-K path is compared with. */
+int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype t, int32_t* idx, int32_t* count,
+                            void* stream);
+
 /* Kernel launch tuning for experiments (host state, not thread-safe; set it before sizing a
  * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
  * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,

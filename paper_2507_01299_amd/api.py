@@ -69,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.larosa_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Layer), i]
         L.larosa_layer_forward.argtypes = [ctypes.POINTER(_Layer), vp, vp, i, ctypes.POINTER(_Trace), vp, sz, vp]
         L.larosa_set_tuning.argtypes = [i, i]
+        L.larosa_quantize_w4.argtypes = [vp, i, i, i, vp, vp, vp]
+        L.larosa_sparse_gemv_w4.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.larosa_threshold_select.argtypes = [vp, i, i, ctypes.c_float, i, vp, vp, vp]
         L.larosa_offline_workspace_bytes.restype = sz
         L.larosa_offline_workspace_bytes.argtypes = [i, i]
         L.larosa_second_moment.argtypes = [vp, i, i, i, vp, i, vp]
@@ -165,6 +168,35 @@ def sparse_gemv(Wp, h, idx, y, dtype, ws: Workspace):
     _check(lib().larosa_sparse_gemv(_ptr(Wp), _ptr(h), _ptr(idx), _ptr(y), B, d_in, d_out, K, dtype_code(dtype),
                                     ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_sparse_gemv")
     return y
+
+
+def quantize_w4(W, dtype):
+    """Round-to-nearest 4-bit codes (int32 [d_in, d_out/8], eight nibbles per dword) and 16-bit scales
+    [d_in, ceil(d_out/128)] of W [d_in, d_out]."""
+    d_in, d_out = W.shape
+    Wq = torch.empty(d_in, d_out // 8, dtype=torch.int32, device=W.device)
+    scales = torch.empty(d_in, (d_out + 127) // 128, dtype=W.dtype, device=W.device)
+    _check(lib().larosa_quantize_w4(_ptr(W), d_in, d_out, dtype_code(dtype), _ptr(Wq), _ptr(scales), _stream()),
+           "larosa_quantize_w4")
+    return Wq, scales
+
+
+def sparse_gemv_w4(Wq, scales, h, idx, y, dtype, ws: Workspace):
+    B, d_in = h.shape
+    d_out = Wq.shape[1] * 8
+    K = d_in if idx is None else idx.shape[1]
+    _check(lib().larosa_sparse_gemv_w4(_ptr(Wq), _ptr(scales), _ptr(h), _ptr(idx), _ptr(y), B, d_in, d_out, K,
+                                       dtype_code(dtype), ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()),
+           "larosa_sparse_gemv_w4")
+    return y
+
+
+def threshold_select(h, eps: float, idx, count, dtype):
+    """idx [B, d] int32, count [B] int32: per token the ascending channels with |h| > eps."""
+    B, d = h.shape
+    _check(lib().larosa_threshold_select(_ptr(h), B, d, float(eps), dtype_code(dtype), _ptr(idx), _ptr(count),
+                                         _stream()), "larosa_threshold_select")
+    return idx, count
 
 
 class OfflineScratch:

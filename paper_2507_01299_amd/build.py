@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblarosa.so")
-SOURCES = ["api.hip", "gemv.hip", "fused.hip", "batched.hip", "topk.hip", "elementwise.hip", "offline.hip"]
+SOURCES = ["api.hip", "gemv.hip", "fused.hip", "batched.hip", "topk.hip", "elementwise.hip", "offline.hip", "w4.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -600,6 +600,57 @@ int larosa_residual_adapter(const float* Q_l, const float* Q_next, int d, larosa
   return launch_contraction(a, true, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
+// ---- 4-bit weights and the threshold sparsifier ------------------------------------------------
+
+int larosa_quantize_w4(const void* W, int d_in, int d_out, larosa_dtype t, void* Wq, void* scales, void* stream) {
+  if (!W || !Wq || !scales || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(W, 16) || !aligned(Wq, 16) || !aligned(scales, 2)) return LAROSA_EINVAL;
+  if (d_in < 1 || d_in > 65535 || d_out < 8 || d_out % 8) return LAROSA_EINVAL;
+  return launch_quantize_w4(static_cast<const uint16_t*>(W), d_in, d_out, static_cast<uint32_t*>(Wq),
+                            static_cast<uint16_t*>(scales), t == LAROSA_BF16,
+                            static_cast<hipStream_t>(stream)) == hipSuccess
+             ? LAROSA_OK
+             : LAROSA_EHIP;
+}
+
+int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, const int32_t* idx, void* y, int B,
+                          int d_in, int d_out, int K, larosa_dtype t, void* ws, size_t ws_bytes, void* stream) {
+  if (!Wq || !scales || !h || !y || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(Wq, 16) || !aligned(scales, 2) || !aligned(h, 16) || !aligned(y, 16) || (idx && !aligned(idx, 4)))
+    return LAROSA_EINVAL;
+  if (int rc = check_gemv_shapes(B, d_in, d_out, K)) return rc;
+  if (!idx && K != d_in) return LAROSA_EINVAL;
+  W4Args w{};
+  GemvArgs& a = w.g;
+  a.h = static_cast<const uint16_t*>(h);
+  a.idx = idx;
+  a.y = static_cast<uint16_t*>(y);
+  a.d_in = d_in; a.d_out = d_out; a.K = K; a.B = B;
+  w.Wq = static_cast<const uint32_t*>(Wq);
+  w.scales = static_cast<const uint16_t*>(scales);
+  w.ng = (d_out + 127) / 128;
+  const GemvPlan p = plan_gemv(d_out, K);
+  if (static_cast<size_t>(B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  const size_t need = kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  a.chunk = p.chunk; a.G = p.G; a.nstrips = p.nstrips;
+  a.counters = static_cast<unsigned*>(ws);
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  return launch_gemv_w4(w, t == LAROSA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+}
+
+int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype t, int32_t* idx, int32_t* count,
+                            void* stream) {
+  if (!h || !idx || !count || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (!aligned(h, 16) || !aligned(idx, 4) || !aligned(count, 4)) return LAROSA_EINVAL;
+  if (B < 1 || d < 8 || d % 8 || !(eps >= 0.f)) return LAROSA_EINVAL;
+  if (d > kMaxTopkD || B > 65535) return LAROSA_EUNSUPPORTED;
+  return launch_threshold_select(static_cast<const uint16_t*>(h), B, d, eps, idx, count, t == LAROSA_BF16,
+                                 static_cast<hipStream_t>(stream)) == hipSuccess
+             ? LAROSA_OK
+             : LAROSA_EHIP;
+}
+
 int larosa_set_tuning(int key, int value) {
   switch (key) {
     case 0:

@@ -47,6 +47,19 @@ Tuning& tuning();
 GemvPlan plan_gemv(int d_out, int K);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
 
+// The same mat-vec over 4-bit weights (w4.hip): g.W is unused; the row loop reads packed codes and
+// per-row, per-128-column scales.
+struct W4Args {
+  GemvArgs g;
+  const uint32_t* Wq;         // [d_in, d_out/8] dwords, nibble k of dword m = code of column 8m+k
+  const uint16_t* scales;     // [d_in, ng] 16-bit, weight = (code - 8) * scale
+  int ng;                     // ceil(d_out / 128)
+};
+hipError_t launch_gemv_w4(const W4Args& w, bool bf16, hipStream_t s);
+// round-to-nearest codes and scales of a 16-bit weight [d_in, d_out]
+hipError_t launch_quantize_w4(const uint16_t* W, int d_in, int d_out, uint32_t* Wq, uint16_t* scales, bool bf16,
+                              hipStream_t s);
+
 // Column-sparse projection with the Top-K select fused into its prologue: the kept list is
 // built inside every workgroup from the block's input vector.
 enum : int { kSrcPlain = 0, kSrcGqa = 1, kSrcSilu = 2, kSrcNorm = 3 };
@@ -94,6 +107,10 @@ hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C,
 // receives h with the dropped channels set to zero.
 hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
                        hipStream_t s);
+
+// Magnitude-threshold sparsifier: idx[b, 0..count[b]) = ascending channels with |h[b,i]| > eps; idx rows are d apart.
+hipError_t launch_threshold_select(const uint16_t* h, int B, int d, float eps, int32_t* idx, int32_t* count, bool bf16,
+                                   hipStream_t s);
 
 // h2[b,i] = v-part of qkv for the GQA group of query head i/head_dim (context-length-1 attention).
 hipError_t launch_gqa_expand(const uint16_t* qkv, uint16_t* h2, int B, int d_q, int d_kv, int head_dim,

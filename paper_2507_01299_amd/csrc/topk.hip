@@ -61,7 +61,76 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   }
 }
 
+// Magnitude-threshold sparsifier (Eq. 4-5), the comparison method with a data-dependent kept count:
+// lane t owns elements [tE, (t+1)E); kept positions come from a block prefix sum of the lanes' counts.
+template <typename T, int E>
+__global__ __launch_bounds__(kTopkThreads) void threshold_kernel(const uint16_t* __restrict__ h, int d, float eps,
+                                                                 int32_t* __restrict__ idx,
+                                                                 int32_t* __restrict__ count) {
+  __shared__ unsigned wave_total[kTopkWaves];
+  const int b = blockIdx.x;
+  const uint16_t* hb = h + static_cast<size_t>(b) * d;
+  const int base = threadIdx.x * E;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  unsigned keep = 0;     // bit q: element base + q is kept
+  unsigned n = 0;
+#pragma unroll
+  for (int q = 0; q < E / 4; ++q) {
+    const int i = base + q * 4;
+    if (i < d) {
+      const uint2 v = *reinterpret_cast<const uint2*>(hb + i);
+      const uint16_t r[4] = {static_cast<uint16_t>(v.x & 0xFFFFu), static_cast<uint16_t>(v.x >> 16),
+                             static_cast<uint16_t>(v.y & 0xFFFFu), static_cast<uint16_t>(v.y >> 16)};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (T::to_f32(r[k] & 0x7FFFu) > eps) {
+          keep |= 1u << (q * 4 + k);
+          n += 1;
+        }
+      }
+    }
+  }
+  const unsigned incl = wave_scan_inclusive(n, lane);
+  if (lane == 63) wave_total[wv] = incl;
+  __syncthreads();
+  unsigned before = incl - n, total = 0;
+#pragma unroll
+  for (int w2 = 0; w2 < kTopkWaves; ++w2) {
+    const unsigned tw = wave_total[w2];
+    if (w2 < wv) before += tw;
+    total += tw;
+  }
+  int32_t* idxb = idx + static_cast<size_t>(b) * d;
+#pragma unroll
+  for (int q = 0; q < E; ++q) {
+    if (keep & (1u << q)) idxb[before++] = base + q;
+  }
+  if (threadIdx.x == 0) count[b] = static_cast<int32_t>(total);
+}
+
+template <typename T>
+hipError_t launch_threshold_t(const uint16_t* h, int B, int d, float eps, int32_t* idx, int32_t* count, hipStream_t s) {
+  dim3 grid(B), block(kTopkThreads);
+  const int e = (d + kTopkThreads - 1) / kTopkThreads;
+  if (e <= 4)
+    hipLaunchKernelGGL((threshold_kernel<T, 4>), grid, block, 0, s, h, d, eps, idx, count);
+  else if (e <= 8)
+    hipLaunchKernelGGL((threshold_kernel<T, 8>), grid, block, 0, s, h, d, eps, idx, count);
+  else if (e <= 16)
+    hipLaunchKernelGGL((threshold_kernel<T, 16>), grid, block, 0, s, h, d, eps, idx, count);
+  else if (e <= 32)
+    hipLaunchKernelGGL((threshold_kernel<T, 32>), grid, block, 0, s, h, d, eps, idx, count);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_threshold_select(const uint16_t* h, int B, int d, float eps, int32_t* idx, int32_t* count, bool bf16,
+                                   hipStream_t s) {
+  return bf16 ? launch_threshold_t<BF16>(h, B, d, eps, idx, count, s) : launch_threshold_t<F16>(h, B, d, eps, idx, count, s);
+}
 
 hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
                        hipStream_t s) {

@@ -1,0 +1,166 @@
+// Column-sparse projection over 4-bit weights (W4A16): the row-streaming mat-vec of gemv.hip with
+// the kept rows read as packed 4-bit codes and dequantised in registers.  The paper shows that the
+// method keeps its accuracy on 4-bit weights (Sec. 5.4, Table 9) and leaves a kernel that does
+// both to future work; the storage format below is this library's own.
+//
+// Format.  Row j of the input-channel-major weight [d_in, d_out] is d_out / 8 dwords; nibble k
+// (bits 4k .. 4k+3) of dword m holds the code q of column 8 m + k, and the weight is
+// (q - 8) * s[j, (8 m + k) / 128] with one 16-bit scale per row and per group of 128 output columns
+// (round-to-nearest codes, symmetric).  Groups run along a row, so the scale folds into the
+// row's coefficient: y[o] = sum_t (h_t s_t,g(o)) (q_t,o - 8).
+//
+// Geometry is that of the 16-bit kernel: a wave owns 512 output columns, a lane 8 of them (one
+// dword per kept row, 256-byte bursts), 16 rows in flight; the -8 offset is applied once per lane
+// as -8 * sum of coefficients.  Reductions, cross-workgroup hand-off and epilogue are shared.
+#include "gemv_core.hpp"
+
+namespace larosa {
+
+namespace {
+
+constexpr int kW4Unroll = 16;
+constexpr int kW4Group = 128;
+
+__device__ __forceinline__ uint32_t load_stream4(const uint32_t* p) { return __builtin_nontemporal_load(p); }
+
+template <typename T, typename Rows>
+__device__ __forceinline__ void stream_rows_w4(const uint32_t* __restrict__ wcol, int row_dwords,
+                                               const uint16_t* __restrict__ scol, int ng, const Rows& rows, int ra,
+                                               int re, float (&acc)[8]) {
+  float csum = 0.f;
+  for (int t = ra; t < re; t += kW4Unroll) {
+    int j[kW4Unroll];
+    uint32_t v[kW4Unroll];
+    uint16_t s[kW4Unroll];
+#pragma unroll
+    for (int u = 0; u < kW4Unroll; ++u) j[u] = rows.row(min(t + u, re - 1));
+#pragma unroll
+    for (int u = 0; u < kW4Unroll; ++u) {
+      v[u] = load_stream4(wcol + static_cast<size_t>(j[u]) * row_dwords);
+      s[u] = scol[static_cast<size_t>(j[u]) * ng];
+    }
+#pragma unroll
+    for (int u = 0; u < kW4Unroll; ++u) {
+      float c = rows.coef(min(t + u, re - 1), j[u]) * T::to_f32(s[u]);
+      c = (t + u < re) ? c : 0.f;
+      csum += c;
+      const uint32_t lo = v[u] & 0x0F0F0F0Fu;          // nibbles 0, 2, 4, 6 as bytes
+      const uint32_t hi = (v[u] >> 4) & 0x0F0F0F0Fu;   // nibbles 1, 3, 5, 7
+      acc[0] = fmaf(c, static_cast<float>(lo & 0xFFu), acc[0]);
+      acc[1] = fmaf(c, static_cast<float>(hi & 0xFFu), acc[1]);
+      acc[2] = fmaf(c, static_cast<float>((lo >> 8) & 0xFFu), acc[2]);
+      acc[3] = fmaf(c, static_cast<float>((hi >> 8) & 0xFFu), acc[3]);
+      acc[4] = fmaf(c, static_cast<float>((lo >> 16) & 0xFFu), acc[4]);
+      acc[5] = fmaf(c, static_cast<float>((hi >> 16) & 0xFFu), acc[5]);
+      acc[6] = fmaf(c, static_cast<float>(lo >> 24), acc[6]);
+      acc[7] = fmaf(c, static_cast<float>(hi >> 24), acc[7]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) acc[k] = fmaf(-8.0f, csum, acc[k]);
+}
+
+template <typename T, int RW, bool INDEXED>
+__global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
+  __shared__ GemvShared<RW> sh;
+  const GemvArgs& a = w.g;
+  const int lane = threadIdx.x & 63;
+  const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const int b = blockIdx.y;
+  const int g = blockIdx.x;
+  const int K = a.K;
+
+  GlobalRows<T, INDEXED> rows;
+  rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
+  rows.h = a.h + static_cast<size_t>(b) * a.d_in;
+  rows.coef_scale = a.coef_scale;
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+  const int row_dwords = a.d_out / 8;
+
+  int f0 = g * a.chunk;
+  const int f1 = min(f0 + a.chunk, a.nstrips * K);
+  Segment sg{f0 / K, 0, 0};
+  sg.t0 = f0 - sg.s * K;
+  int seg_no = 0;
+  while (f0 < f1) {
+    sg.t1 = min(K, sg.t0 + (f1 - f0));
+    const int col = sg.s * kStripCols + lane * 8;
+    float acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+    const int n = sg.t1 - sg.t0;
+    const int per = (n + RW - 1) / RW;
+    const int ra = sg.t0 + rw * per;
+    const int re = min(sg.t1, ra + per);
+    if (col < a.d_out)
+      stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+    reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
+                             rw);
+    f0 += sg.t1 - sg.t0;
+    sg.s += 1;
+    sg.t0 = 0;
+    seg_no += 1;
+  }
+}
+
+// Round-to-nearest quantiser: one wave per row and 512 columns, a lane holds 8 columns, 16 lanes
+// share a group.  s = max|w| / 7 rounded to 16 bits, q = clip(rint(w / s), -8, 7) + 8.
+template <typename T>
+__global__ __launch_bounds__(64) void quantize_w4_kernel(const uint16_t* __restrict__ W, int d_out, int ng,
+                                                         uint32_t* __restrict__ Wq, uint16_t* __restrict__ scales) {
+  const int lane = threadIdx.x;
+  const int row = blockIdx.y;
+  const int col = blockIdx.x * kStripCols + lane * 8;
+  float w[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) w[k] = 0.f;
+  if (col < d_out) unpack8<T>(*reinterpret_cast<const uint4*>(W + static_cast<size_t>(row) * d_out + col), w);
+  float m = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(w[k]));
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
+  const uint16_t sb = T::from_f32(m / 7.0f);
+  const float s = T::to_f32(sb);
+  uint32_t packed = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float q = 0.f;
+    if (s > 0.f) q = fminf(fmaxf(rintf(w[k] / s), -8.f), 7.f);
+    packed |= static_cast<uint32_t>(static_cast<int>(q) + 8) << (4 * k);
+  }
+  if (col < d_out) {
+    Wq[static_cast<size_t>(row) * (d_out / 8) + col / 8] = packed;
+    if ((lane & 15) == 0) scales[static_cast<size_t>(row) * ng + col / kW4Group] = sb;
+  }
+}
+
+template <typename T>
+hipError_t launch_w4_t(const W4Args& w, hipStream_t st) {
+  constexpr int RW = 8;
+  dim3 grid(w.g.G, w.g.B), block(RW * 64);
+  if (w.g.idx)
+    hipLaunchKernelGGL((gemv_rows_w4_kernel<T, RW, true>), grid, block, 0, st, w);
+  else
+    hipLaunchKernelGGL((gemv_rows_w4_kernel<T, RW, false>), grid, block, 0, st, w);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quantize_w4(const uint16_t* W, int d_in, int d_out, uint32_t* Wq, uint16_t* scales, bool bf16,
+                              hipStream_t s) {
+  const int ng = (d_out + kW4Group - 1) / kW4Group;
+  dim3 grid((d_out + kStripCols - 1) / kStripCols, d_in), block(64);
+  if (bf16)
+    hipLaunchKernelGGL(quantize_w4_kernel<BF16>, grid, block, 0, s, W, d_out, ng, Wq, scales);
+  else
+    hipLaunchKernelGGL(quantize_w4_kernel<F16>, grid, block, 0, s, W, d_out, ng, Wq, scales);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemv_w4(const W4Args& w, bool bf16, hipStream_t s) {
+  return bf16 ? launch_w4_t<BF16>(w, s) : launch_w4_t<F16>(w, s);
+}
+
+}  // namespace larosa

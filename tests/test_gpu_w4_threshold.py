@@ -1,0 +1,145 @@
+"""GPU parity, through the C ABI, of the 4-bit-weight projection (quantiser: codes and scales equal
+to the oracle's bit for bit; projection within 2e-3 relative L2 of the oracle's rounded output) and of
+the magnitude-threshold sparsifier (indices and counts equal)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import larosa_oracle as O
+from paper_2507_01299_amd import synth
+from tests.gpu_util import REL_L2_TOL, rel_l2, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api(gpu_device):
+    from paper_2507_01299_amd import api as A
+    A.lib()
+    return A
+
+
+@pytest.fixture(scope="module")
+def ws(api):
+    return api.workspace(4, 32768, 32768, 32768)
+
+
+def _heavy(rng, B, d, dtype):
+    v = rng.standard_normal((B, d)) * (np.arange(1, d + 1) ** -0.6)[None, :]
+    v[:, rng.choice(d, min(4, d), replace=False)] *= 20
+    bits = O.encode16(v, dtype)
+    return bits, O.decode16(bits, dtype)
+
+
+def _dev_w4(codes, sbits, dtype):
+    packed = O.pack_w4(codes)
+    return torch.from_numpy(packed.view(np.int32)).cuda(), to_dev(sbits, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d_in,d_out", [(37, 328), (64, 1024), (5, 8), (33, 704), (130, 1160)])
+def test_quantiser_equals_oracle_bit_for_bit(api, dtype, d_in, d_out):
+    print(f"quantize_w4 dtype={dtype} {d_in}x{d_out}", flush=True)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, 21 + d_out), dtype)
+    wb[0, :min(128, d_out)] = 0                                   # a zero group
+    Wq, sc = api.quantize_w4(to_dev(wb, dtype), dtype)
+    torch.cuda.synchronize()
+    codes, sbits = O.quantize_rtn_w4(O.decode16(wb, dtype), dtype)
+    assert np.array_equal(to_bits(sc), sbits)
+    assert np.array_equal(Wq.cpu().numpy().view(np.uint32), O.pack_w4(codes))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d_in,d_out,K", [(1, 512, 1024, 256), (3, 1096, 1160, 700), (1, 64, 8, 64), (2, 2048, 4096, 1),
+                                            (1, 1000, 6144, 613)])
+def test_w4_projection_matches_oracle(api, ws, dtype, B, d_in, d_out, K):
+    print(f"sparse_gemv_w4 dtype={dtype} B={B} {d_in}x{d_out} K={K}", flush=True)
+    rng = np.random.default_rng(300 + d_in + K)
+    codes, sbits = O.quantize_rtn_w4(synth.gaussian_weight(d_in, d_out, 31 + d_in), dtype)
+    Wq, sc = _dev_w4(codes, sbits, dtype)
+    hb, h = _heavy(rng, B, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    y = torch.zeros(B, d_out, dtype=api.torch_dtype(dtype), device="cuda:0")
+    api.sparse_gemv_w4(Wq, sc, to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+    torch.cuda.synchronize()
+    got = O.decode16(to_bits(y), dtype)
+    for b in range(B):
+        want = O.round16(O.sparse_project_w4(h[b], idx[b], codes, sbits, dtype), dtype)
+        assert rel_l2(got[b], want) <= REL_L2_TOL
+    # all rows, no index list
+    api.sparse_gemv_w4(Wq, sc, to_dev(hb, dtype), None, y, dtype, ws)
+    torch.cuda.synchronize()
+    got = O.decode16(to_bits(y), dtype)
+    deq = O.dequantize_w4(codes, sbits, dtype)
+    for b in range(B):
+        assert rel_l2(got[b], O.round16(h[b] @ deq, dtype)) <= REL_L2_TOL
+    # same call twice: same bits
+    y2 = torch.zeros_like(y)
+    api.sparse_gemv_w4(Wq, sc, to_dev(hb, dtype), None, y2, dtype, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_w4_projection_full_size_gate_up(api, ws):
+    """gate|up of the 7B-shaped layer (4096 x 22016, 40 % sparsity) in the launch shape the bench times."""
+    dtype, d_in, d_out, K = "f16", 4096, 22016, 2458
+    print("sparse_gemv_w4 full size", flush=True)
+    rng = np.random.default_rng(77)
+    wb = O.encode16(synth.gaussian_weight(d_in, d_out, 41), dtype)
+    Wq, sc = api.quantize_w4(to_dev(wb, dtype), dtype)          # checked bit for bit above; reused here as input
+    torch.cuda.synchronize()
+    codes = O.unpack_w4(Wq.cpu().numpy().view(np.uint32))
+    sbits = to_bits(sc)
+    rows = np.sort(rng.choice(d_in, 16, replace=False))
+    c_or, s_or = O.quantize_rtn_w4(O.decode16(wb[rows], dtype), dtype)
+    assert np.array_equal(codes[rows], c_or) and np.array_equal(sbits[rows], s_or)
+    hb, h = _heavy(rng, 1, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    y = torch.zeros(1, d_out, dtype=torch.float16, device="cuda:0")
+    api.sparse_gemv_w4(Wq, sc, to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+    torch.cuda.synchronize()
+    want = O.round16(O.sparse_project_w4(h[0], idx[0], codes, sbits, dtype), dtype)
+    assert rel_l2(O.decode16(to_bits(y), dtype)[0], want) <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,d", [(1, 8), (3, 1096), (2, 4096), (1, 11008), (1, 32768)])
+def test_threshold_select_equals_oracle(api, dtype, B, d):
+    print(f"threshold_select dtype={dtype} B={B} d={d}", flush=True)
+    rng = np.random.default_rng(500 + d)
+    hb, h = _heavy(rng, B, d, dtype)
+    cal = _heavy(rng, 8, d, dtype)[1]
+    idx = torch.full((B, d), -1, dtype=torch.int32, device="cuda:0")
+    cnt = torch.full((B,), -1, dtype=torch.int32, device="cuda:0")
+    eps_list = [np.float32(O.calibrate_threshold(cal, p)) for p in (0.25, 0.4, 0.5)]
+    eps_list += [np.float32(0.0), np.float32(1e30), np.float32(abs(h[0, d // 2]))]     # the last one: an exact tie
+    for eps in eps_list:
+        idx.fill_(-1)
+        api.threshold_select(to_dev(hb, dtype), float(eps), idx, cnt, dtype)
+        torch.cuda.synchronize()
+        gi, gc = idx.cpu().numpy(), cnt.cpu().numpy()
+        for b in range(B):
+            want = O.threshold_indices(h[b], float(eps))
+            assert gc[b] == want.size
+            assert np.array_equal(gi[b, :want.size], want)
+            assert np.all(gi[b, want.size:] == -1)                # nothing written past the count
+
+
+def test_threshold_then_projection_is_the_masked_product(api, ws):
+    """S_eps(h) W with the kept count read back: the variable-K comparison path (Eq. 3-5)."""
+    dtype, d, d_out = "f16", 1096, 1160
+    rng = np.random.default_rng(900)
+    wb = O.encode16(synth.gaussian_weight(d, d_out, 51), dtype)
+    W = O.decode16(wb, dtype)
+    hb, h = _heavy(rng, 1, d, dtype)
+    eps = np.float32(O.calibrate_threshold(_heavy(rng, 8, d, dtype)[1], 0.4))
+    idx = torch.zeros(1, d, dtype=torch.int32, device="cuda:0")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    api.threshold_select(to_dev(hb, dtype), float(eps), idx, cnt, dtype)
+    K = int(cnt.item())
+    assert 0 < K < d
+    y = torch.zeros(1, d_out, dtype=torch.float16, device="cuda:0")
+    api.sparse_gemv(to_dev(wb, dtype), to_dev(hb, dtype), idx[:, :K].contiguous(), y, dtype, ws)
+    torch.cuda.synchronize()
+    masked = np.where(np.abs(h[0]) > float(eps), h[0], 0.0)
+    assert rel_l2(O.decode16(to_bits(y), dtype)[0], O.round16(masked @ W, dtype)) <= REL_L2_TOL

@@ -104,3 +104,25 @@ def test_offline_calls_reject_invalid_arguments(lib):
     assert lib.larosa_fold_output(fake, fake, 12, 64, 0, other, fake, big, None) == api.EINVAL
     assert lib.larosa_residual_adapter(fake, fake, 64, 2, other, fake, big, None) == api.EINVAL
     assert lib.larosa_residual_adapter(fake, fake, 64, 1, other, fake, 3 * 64 * 64 * 2, None) == api.EWORKSPACE
+
+
+def test_w4_and_threshold_calls_reject_invalid_arguments(lib):
+    from paper_2507_01299_amd import api
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1002)
+    big = 1 << 24
+    assert lib.larosa_quantize_w4(None, 8, 64, 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_quantize_w4(fake, 8, 60, 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_quantize_w4(fake, 0, 64, 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_quantize_w4(fake, 8, 64, 3, fake, fake, None) == api.EINVAL
+    assert lib.larosa_sparse_gemv_w4(fake, None, fake, fake, fake, 1, 64, 64, 8, 0, fake, big, None) == api.EINVAL
+    assert lib.larosa_sparse_gemv_w4(fake, fake, fake, None, fake, 1, 64, 64, 8, 0, fake, big, None) == api.EINVAL
+    assert lib.larosa_sparse_gemv_w4(fake, fake, fake, fake, fake, 1, 64, 64, 65, 0, fake, big, None) == api.EINVAL
+    assert lib.larosa_sparse_gemv_w4(fake, fake, odd, fake, fake, 1, 64, 64, 8, 0, fake, big, None) == api.EINVAL
+    assert lib.larosa_sparse_gemv_w4(fake, fake, fake, fake, fake, 1, 64, 64, 8, 0, fake, 16, None) == api.EWORKSPACE
+    f = ctypes.c_float
+    assert lib.larosa_threshold_select(None, 1, 64, f(0.1), 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_threshold_select(fake, 1, 60, f(0.1), 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_threshold_select(fake, 1, 64, f(-1.0), 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_threshold_select(fake, 1, 64, f(float("nan")), 0, fake, fake, None) == api.EINVAL
+    assert lib.larosa_threshold_select(fake, 1, 65536, f(0.1), 0, fake, fake, None) == api.EUNSUPPORTED
