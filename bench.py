@@ -117,6 +117,173 @@ def offline_report(args, api, torch, shape, cfg, dev):
     print(json.dumps(report), flush=True)
 
 
+def _graph_event_us(torch, fn, launches, reps):
+    """Average microseconds per launch of fn's launches, replayed as one HIP graph."""
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        fn()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * launches)
+
+
+def _heavy_tokens(torch, gen, B, d, td, dev):
+    """Rotated-activation stand-in: Gaussian entries with an i^-0.6 envelope and 4 outlier channels."""
+    env = torch.arange(1, d + 1, device=dev, dtype=torch.float32) ** -0.6
+    h = torch.randn(B, d, generator=gen, device=dev, dtype=torch.float32) * env
+    h[:, torch.randperm(d, generator=gen, device=dev)[:4]] *= 20.0
+    return h.to(td).contiguous()
+
+
+def w4_report(args, api, torch, shape, cfg, dev):
+    """The four column-sparse projections of one layer (indices given) over 4-bit weights and over the
+    16-bit weights they were quantised from, B = 1.  Bytes per launch: K (d_out / 2 + 2 ceil(d_out / 128))
+    for codes and scales of the kept rows."""
+    td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
+    d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff
+    p, nsets = args.sparsity, max(1, args.nsets)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1299)
+    dims = [("qkv", d, d_q + 2 * d_kv), ("o", d_q, d), ("gu", d, 2 * d_ff), ("down", d_ff, d)]
+    ws = api.workspace(1, max(d, d_ff), 2 * d_ff, max(d, d_ff))
+    rows = {}
+    tot16 = tot4 = bytes16 = bytes4 = 0.0
+    reps = max(1, args.steps // nsets)
+    for name, din, dout in dims:
+        K = int(round((1 - p) * din))
+        W16 = [(torch.randn(din, dout, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(td)
+               for _ in range(nsets)]
+        W4 = [api.quantize_w4(w, shape.dtype) for w in W16]
+        h = _heavy_tokens(torch, gen, 1, din, td, dev)
+        idx = torch.empty(1, K, dtype=torch.int32, device=dev)
+        api.topk(h, K, idx, shape.dtype)
+        y = torch.zeros(1, dout, dtype=td, device=dev)
+
+        def run16():
+            for w in W16:
+                api.sparse_gemv(w, h, idx, y, shape.dtype, ws)
+
+        def run4():
+            for wq, sc in W4:
+                api.sparse_gemv_w4(wq, sc, h, idx, y, shape.dtype, ws)
+
+        us16 = _graph_event_us(torch, run16, nsets, reps)
+        us4 = _graph_event_us(torch, run4, nsets, reps)
+        b16 = 2.0 * K * dout
+        b4 = K * (dout / 2 + 2 * ((dout + 127) // 128))
+        rows[name] = dict(K=K, d_out=dout, us_16bit=round(us16, 3), us_w4=round(us4, 3),
+                          GBs_16bit=round(b16 / us16 / 1e3, 1), GBs_w4=round(b4 / us4 / 1e3, 1))
+        tot16 += us16; tot4 += us4; bytes16 += b16; bytes4 += b4
+        del W16, W4
+    ach = bytes4 / 4 / (tot4 / 4) / 1e3
+    report = {
+        "metric": "us_per_layer_sparse_projections_w4", "value": round(tot4, 3), "unit": "us", "n_gpus": 1,
+        "steps": reps * nsets, "warmup": 1, "ms_per_step": round(tot4 / 1e3, 6), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"four column-sparse projections of one {shape.name} layer over 4-bit weights, "
+                               f"batch 1, sparsity {p}", "shape": shape.name, "weight_sets": nsets},
+        "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "gemv_rows_w4_kernel (codes + scales of the kept rows, average over the 4 launches)"},
+        "cpu_baseline": None,
+        "extra": {"per_projection": rows, "us_per_layer_16bit": round(tot16, 3),
+                  "speedup_w4_vs_16bit": round(tot16 / tot4, 3),
+                  "bytes_per_layer_w4": bytes4, "bytes_per_layer_16bit": bytes16},
+    }
+    print(json.dumps(report), flush=True)
+
+
+def threshold_report(args, api, torch, shape, cfg, dev):
+    """Sec. 4.1 on synthetic tokens: a cutoff calibrated offline for the target sparsity against Top-K
+    at the same target, on a stream whose per-token scale drifts (log-normal, sigma 0.3).  For every
+    token: kept count, and the time of the gate|up-shaped column-sparse projection with that count
+    (eager launches, HIP events, median of 7 runs per token)."""
+    import numpy as np
+    td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
+    d, dout, p = shape.d, 2 * shape.d_ff, args.sparsity
+    n_tok = max(16, min(args.steps, 512))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1299)
+    nsets = max(1, args.nsets)
+    Ws = [(torch.randn(d, dout, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(td) for _ in range(nsets)]
+    ws = api.workspace(1, d, dout, d)
+    cal = _heavy_tokens(torch, gen, 512, d, td, dev)
+    eps = float(torch.quantile(cal.float().abs().flatten()[: 1 << 20], p))       # offline calibrated cutoff
+    drift = torch.exp(0.3 * torch.randn(n_tok, generator=gen, device=dev))
+    toks = (_heavy_tokens(torch, gen, n_tok, d, td, dev).float() * drift[:, None]).to(td).contiguous()
+    K = int(round((1 - p) * d))
+    y = torch.zeros(1, dout, dtype=td, device=dev)
+    idx_t = torch.zeros(1, d, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    idx_k = torch.zeros(1, K, dtype=torch.int32, device=dev)
+
+    def timed(fn, rep=7):
+        """Median of `rep` event-timed runs: the spread over tokens should show the kept count, not
+        launch jitter."""
+        ts = []
+        for _ in range(rep):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3)
+        return sorted(ts)[rep // 2]
+
+    t_thr, t_top, kept = [], [], []
+    for rnd in range(2):                       # first round warms up
+        t_thr.clear(); t_top.clear(); kept.clear()
+        for i in range(n_tok if rnd else min(n_tok, 16)):
+            h = toks[i:i + 1]
+            W = Ws[i % nsets]
+            api.threshold_select(h, eps, idx_t, cnt, shape.dtype)
+            k_i = int(cnt.item())               # the projection's launch shape depends on the count
+            kept.append(k_i)
+            if k_i > 0:
+                sel = idx_t[:, :k_i].contiguous()
+                t_thr.append(timed(lambda: api.sparse_gemv(W, h, sel, y, shape.dtype, ws)))
+            else:
+                t_thr.append(0.0)
+
+            def topk_path():
+                api.topk(h, K, idx_k, shape.dtype)
+                api.sparse_gemv(W, h, idx_k, y, shape.dtype, ws)
+            t_top.append(timed(topk_path))
+
+    def stats(v):
+        a = np.asarray(v, np.float64)
+        return dict(mean=round(float(a.mean()), 3), std=round(float(a.std()), 3), min=round(float(a.min()), 3),
+                    p10=round(float(np.percentile(a, 10)), 3), p90=round(float(np.percentile(a, 90)), 3),
+                    max=round(float(a.max()), 3))
+
+    frac = np.asarray(kept) / d
+    report = {
+        "metric": "per_token_us_spread_threshold_vs_topk", "value": stats(t_thr)["std"], "unit": "us (std over tokens)",
+        "n_gpus": 1, "steps": n_tok, "warmup": n_tok, "ms_per_step": round(float(np.mean(t_thr)) / 1e3, 6),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"gate|up-shaped projection ({d} x {dout}) of {shape.name}, {n_tok} tokens with "
+                               f"log-normal scale drift (sigma 0.3), target sparsity {p}", "shape": shape.name},
+        "roofline": None, "cpu_baseline": None,
+        "extra": {"threshold_eps": eps, "threshold_kept_fraction": stats(frac), "topk_kept_fraction": K / d,
+                  "threshold_projection_us": stats(t_thr), "topk_select_plus_projection_us": stats(t_top),
+                  "note": "threshold time excludes its select kernel and the count read-back; Top-K time includes "
+                          "its select kernel"},
+    }
+    print(json.dumps(report), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +304,12 @@ def main():
     ap.add_argument("--offline", action="store_true",
                     help="time the offline contractions (second moment, folds, adapter) of the chosen "
                          "config's layer instead of the decode step; prints its own JSON line")
+    ap.add_argument("--w4", action="store_true",
+                    help="time the four column-sparse projections of the chosen layer over 4-bit weights "
+                         "next to the 16-bit ones; prints its own JSON line")
+    ap.add_argument("--threshold-comparator", action="store_true",
+                    help="per-token time and kept-count spread of the magnitude-threshold sparsifier against "
+                         "Top-K on a synthetic token stream with scale drift; prints its own JSON line")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="larosa_set_tuning(KEY, VALUE) before anything is sized (experiments)")
     args = ap.parse_args()
@@ -161,6 +334,10 @@ def main():
     shape = synth.SHAPES[cfg["shape"]]
     if args.offline:
         return offline_report(args, api, torch, shape, cfg, dev)
+    if args.w4:
+        return w4_report(args, api, torch, shape, cfg, dev)
+    if args.threshold_comparator:
+        return threshold_report(args, api, torch, shape, cfg, dev)
     td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
     p, B, nsets = args.sparsity, args.batch, max(1, args.nsets)
     d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff
