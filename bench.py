@@ -454,7 +454,7 @@ def main():
     sparse_launch_us = event_time_us(sparse_all, 4 * nsets, reps)
     standalone_launch_us = sparse_launch_us
     stage_us = None
-    if B == 1:
+    if True:
         # The kernel that dominates the timed layer step is the projection with the Top-K fused in
         # (4 launches per step).  Time it inside larosa_layer_forward itself: the library records
         # caller-supplied HIP events at the stage boundaries of each (eagerly launched) step.
@@ -474,7 +474,8 @@ def main():
         for es in evs:
             for k, n in enumerate(names):
                 stage_us[n] += es[k].elapsed_time(es[k + 1]) * 1e3 / n_ev
-        sparse_launch_us = (stage_us["qkv"] + stage_us["o"] + stage_us["gu"] + stage_us["down"]) / 4.0
+        if B == 1:
+            sparse_launch_us = (stage_us["qkv"] + stage_us["o"] + stage_us["gu"] + stage_us["down"]) / 4.0
     # rows a launch has to read: the kept rows at batch 1, the union of the tokens' kept rows otherwise
     U = [int(torch.unique(trace[n]).numel()) for n in ("idx1", "idx2", "idx3", "idx4")]
     sel_bytes_layer = 2 * (U[0] * d_qkv + U[1] * d + U[2] * 2 * d_ff + U[3] * d)

@@ -384,8 +384,13 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, masked, st));
     LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr));
     mark(2);
-    LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
-    LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, masked, st));
+    {
+      TopkSource sc{};
+      sc.mode = kSrcGqa; sc.src = qkv; sc.h_out = h2;
+      sc.d_q = d_q; sc.d_kv = d_kv; sc.head_dim = L->head_dim;
+      sc.group = (d_q / L->head_dim) / (d_kv / L->head_dim);
+      LAROSA_HIP(launch_topk_from(sc, B, d_q, L->K2, idx2, masked, bf, st));
+    }
     LAROSA_TRY(project(L->Wo, d_q, d, x1, x, o));
     mark(3);
     LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
@@ -393,8 +398,11 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, masked, st));
     LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr));
     mark(5);
-    LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
-    LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, masked, st));
+    {
+      TopkSource sc{};
+      sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
+      LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, masked, bf, st));
+    }
     LAROSA_TRY(project(L->Wdown, d_ff, d, x2, x1, down));
     mark(6);
   } else if (tuning().fused) {
@@ -437,8 +445,9 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
                        static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
     } else {
       // a wide intermediate vector makes the per-workgroup selection too long: select once instead
-      LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
-      LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
+      TopkSource sc{};
+      sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
+      LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, nullptr, bf, st));
       LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
     }
     mark(6);

@@ -10,11 +10,14 @@ namespace {
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 
-template <int E>   // elements per lane, multiple of 4
+// Where the selected vector comes from (batched decoder layer): the plain vector, the context-length-1
+// attention output read straight from q|k|v (value head of the query head's group), or
+// R(SiLU(gate) * up) computed from gate|up.  The vector itself can be written out as well.
+template <typename T, int E>   // E elements per lane, multiple of 4
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __restrict__ h, int d, int K,
                                                             int32_t* __restrict__ idx,
                                                             uint16_t* __restrict__ vals,
-                                                            uint16_t* __restrict__ masked) {
+                                                            uint16_t* __restrict__ masked, TopkSource sc) {
   __shared__ TopkShared<kTopkWaves> sm;
   const int b = blockIdx.x;
   const uint16_t* hb = h + static_cast<size_t>(b) * d;
@@ -25,7 +28,31 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   for (int q = 0; q < E / 4; ++q) {
     const int i = base + q * 4;
     uint2 v = make_uint2(0u, 0u);
-    if (i < d) v = *reinterpret_cast<const uint2*>(hb + i);     // d % 4 == 0: all four valid or none
+    if (i < d) {                                                // d % 4 == 0: all four valid or none
+      if (sc.mode == kSrcGqa) {
+        const int head = i / sc.head_dim;
+        const int src = (head / sc.group) * sc.head_dim + (i - head * sc.head_dim);
+        v = *reinterpret_cast<const uint2*>(sc.src + static_cast<size_t>(b) * (sc.d_q + 2 * sc.d_kv) + sc.d_q +
+                                            sc.d_kv + src);
+      } else if (sc.mode == kSrcSilu) {
+        const uint16_t* gb = sc.src + static_cast<size_t>(b) * 2 * d;
+        const uint2 g2 = *reinterpret_cast<const uint2*>(gb + i);
+        const uint2 u2 = *reinterpret_cast<const uint2*>(gb + d + i);
+        float g[4], u[4];
+        T::unpack2(g2.x, g[0], g[1]);
+        T::unpack2(g2.y, g[2], g[3]);
+        T::unpack2(u2.x, u[0], u[1]);
+        T::unpack2(u2.y, u[2], u[3]);
+        uint16_t o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = T::from_f32(silu_f32(g[k]) * u[k]);
+        v.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
+        v.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
+      } else {
+        v = *reinterpret_cast<const uint2*>(hb + i);
+      }
+      if (sc.h_out) *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
+    }
     raw[q * 4 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu);
     raw[q * 4 + 1] = static_cast<uint16_t>(v.x >> 16);
     raw[q * 4 + 2] = static_cast<uint16_t>(v.y & 0xFFFFu);
@@ -132,23 +159,37 @@ hipError_t launch_threshold_select(const uint16_t* h, int B, int d, float eps, i
   return bf16 ? launch_threshold_t<BF16>(h, B, d, eps, idx, count, s) : launch_threshold_t<F16>(h, B, d, eps, idx, count, s);
 }
 
-hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
-                       hipStream_t s) {
+template <typename T>
+hipError_t launch_topk_t(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
+                         const TopkSource& sc, hipStream_t s) {
   dim3 grid(B), block(kTopkThreads);
   const int e = (d + kTopkThreads - 1) / kTopkThreads;
   if (e <= 4)
-    hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, s, h, d, K, idx, vals, masked);
+    hipLaunchKernelGGL((topk_kernel<T, 4>), grid, block, 0, s, h, d, K, idx, vals, masked, sc);
   else if (e <= 8)
-    hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, s, h, d, K, idx, vals, masked);
+    hipLaunchKernelGGL((topk_kernel<T, 8>), grid, block, 0, s, h, d, K, idx, vals, masked, sc);
   else if (e <= 16)
-    hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, s, h, d, K, idx, vals, masked);
+    hipLaunchKernelGGL((topk_kernel<T, 16>), grid, block, 0, s, h, d, K, idx, vals, masked, sc);
   else if (e <= 24)
-    hipLaunchKernelGGL(topk_kernel<24>, grid, block, 0, s, h, d, K, idx, vals, masked);
+    hipLaunchKernelGGL((topk_kernel<T, 24>), grid, block, 0, s, h, d, K, idx, vals, masked, sc);
   else if (e <= 32)
-    hipLaunchKernelGGL(topk_kernel<32>, grid, block, 0, s, h, d, K, idx, vals, masked);
+    hipLaunchKernelGGL((topk_kernel<T, 32>), grid, block, 0, s, h, d, K, idx, vals, masked, sc);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
+                       hipStream_t s) {
+  TopkSource sc{};
+  sc.mode = kSrcPlain;
+  return launch_topk_t<F16>(h, B, d, K, idx, vals, masked, sc, s);   // the type matters for kSrcSilu only
+}
+
+hipError_t launch_topk_from(const TopkSource& sc, int B, int d, int K, int32_t* idx, uint16_t* masked, bool bf16,
+                            hipStream_t s) {
+  return bf16 ? launch_topk_t<BF16>(sc.src, B, d, K, idx, nullptr, masked, sc, s)
+              : launch_topk_t<F16>(sc.src, B, d, K, idx, nullptr, masked, sc, s);
 }
 
 }  // namespace larosa
