@@ -2,8 +2,10 @@
 // calibration tokens, the folded weights Q^T W and W Q, and the residual adapters Q_l^T Q_{l+1}.
 // All four are dense contractions  C[m,n] = sum_k A(k,m) B(k,n)  and share one kernel.
 //
-//  * v_mfma_f32_32x32x16 (f16 / bf16 inputs, fp32 accumulate).  A workgroup of 4 waves owns a 128 x 128
-//    tile of C, each wave a 64 x 64 quarter (2 x 2 instruction tiles, 64 accumulator registers).
+//  * v_mfma_f32_32x32x16 (f16 / bf16 inputs, fp32 accumulate).  A workgroup of 4 waves owns a 256 x 128
+//    tile of C, each wave a 128 x 64 quarter (4 x 2 instruction tiles, 128 accumulator registers): six
+//    operand reads from LDS feed eight instructions.  The global loads of k-tile i + 2 are in flight
+//    while tile i is multiplied and tile i + 1 moves from registers to the other LDS buffer.
 //  * Operands are stored k-major ([k][m], the layout of X, Q and W), the instruction wants 8 values
 //    along k per lane.  The transposition happens on the way into LDS: a lane loads 8 consecutive
 //    columns of two neighbouring k rows, pairs them into dwords (k, k+1) and writes them to a tile
@@ -15,7 +17,8 @@
 //    adds the products of the listed term pairs into the same accumulators.
 //  * 32 concurrent workgroups of an XCD (workgroup i runs on XCD i % 8) form a 4 x 8 patch of tiles,
 //    so the operand panels they stream are shared through that XCD's L2.
-//  * X^T X is symmetric: only tiles on or above the diagonal are computed and each is stored twice.
+//  * X^T X is symmetric: tiles that lie entirely below the diagonal are not computed; their elements are
+//    stored by the tile that computes the mirrored position.
 #include "kernels.hpp"
 #include "numeric.hpp"
 
@@ -28,10 +31,12 @@ typedef __bf16 bfloat8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 128;         // C tile edge per workgroup
+constexpr int kTileM = 256;        // C tile of a workgroup: 256 rows (A columns) x 128 columns
+constexpr int kTileN = 128;
 constexpr int kKTile = 32;         // k rows per LDS stage
 constexpr int kRowDwords = 17;     // 16 k-pairs + 1 pad: odd stride
-constexpr int kTileDwords = kTile * kRowDwords;
+constexpr int kTileDwordsA = kTileM * kRowDwords;
+constexpr int kTileDwordsB = kTileN * kRowDwords;
 constexpr int kPatchM = 4, kPatchN = 8;
 
 template <typename T> struct Mfma;
@@ -47,29 +52,22 @@ template <> struct Mfma<BF16> {
   }
 };
 
-// Registers of one thread for one operand tile in flight.
-struct Staged {
-  uint4 r0, r1;
-};
-
-// k-major source P[k][ld]: rows k0 + 2 kp, k0 + 2 kp + 1, columns c0 + 8 g .. + 7.
-__device__ __forceinline__ Staged load_kmajor(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int c0, int cols,
-                                              int g, int kp) {
-  Staged s;
-  s.r0 = make_uint4(0, 0, 0, 0);
-  s.r1 = s.r0;
+// k-major source P[k][ld]: rows k0 + 2 kp, k0 + 2 kp + 1, columns c0 + 8 g .. + 7 -> r0, r1.
+__device__ __forceinline__ void load_kmajor(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int c0, int cols,
+                                            int g, int kp, uint4& r0, uint4& r1) {
+  r0 = make_uint4(0, 0, 0, 0);
+  r1 = r0;
   const int c = c0 + 8 * g;
   const int k = k0 + 2 * kp;
   if (c < cols) {
-    if (k < Kd) s.r0 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k) * ld + c);
-    if (k + 1 < Kd) s.r1 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k + 1) * ld + c);
+    if (k < Kd) r0 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k) * ld + c);
+    if (k + 1 < Kd) r1 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k + 1) * ld + c);
   }
-  return s;
 }
 
-__device__ __forceinline__ void store_kmajor(uint32_t* tile, const Staged& s, int g, int kp) {
-  const uint32_t a[4] = {s.r0.x, s.r0.y, s.r0.z, s.r0.w};
-  const uint32_t b[4] = {s.r1.x, s.r1.y, s.r1.z, s.r1.w};
+__device__ __forceinline__ void store_kmajor(uint32_t* tile, const uint4& r0, const uint4& r1, int g, int kp) {
+  const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w};
+  const uint32_t b[4] = {r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     tile[(8 * g + 2 * q) * kRowDwords + kp] = (a[q] & 0xFFFFu) | (b[q] << 16);
@@ -77,28 +75,18 @@ __device__ __forceinline__ void store_kmajor(uint32_t* tile, const Staged& s, in
   }
 }
 
-// k-contiguous source P[m][ld]: two 16-byte pieces per thread (items t and t + 256 of 128 rows x 4).
-__device__ __forceinline__ Staged load_kcontig(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int m0, int rows,
-                                               int t) {
-  Staged s;
-  s.r0 = make_uint4(0, 0, 0, 0);
-  s.r1 = s.r0;
-  const int kq = t & 3;
+// k-contiguous source P[m][ld]: 16 bytes (8 k) of row m0 + row at k0 + 8 kq.
+__device__ __forceinline__ uint4 load_kcontig(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int m0, int rows,
+                                              int row, int kq) {
   const int k = k0 + 8 * kq;
-  const int ma = m0 + (t >> 2), mb = ma + 64;
-  if (k < Kd) {
-    if (ma < rows) s.r0 = *reinterpret_cast<const uint4*>(P + static_cast<long>(ma) * ld + k);
-    if (mb < rows) s.r1 = *reinterpret_cast<const uint4*>(P + static_cast<long>(mb) * ld + k);
-  }
-  return s;
+  const int m = m0 + row;
+  if (k < Kd && m < rows) return *reinterpret_cast<const uint4*>(P + static_cast<long>(m) * ld + k);
+  return make_uint4(0, 0, 0, 0);
 }
 
-__device__ __forceinline__ void store_kcontig(uint32_t* tile, const Staged& s, int t) {
-  const int kq = t & 3;
-  uint32_t* pa = tile + (t >> 2) * kRowDwords + 4 * kq;
-  uint32_t* pb = pa + 64 * kRowDwords;
-  pa[0] = s.r0.x; pa[1] = s.r0.y; pa[2] = s.r0.z; pa[3] = s.r0.w;
-  pb[0] = s.r1.x; pb[1] = s.r1.y; pb[2] = s.r1.z; pb[3] = s.r1.w;
+__device__ __forceinline__ void store_kcontig(uint32_t* tile, const uint4& r, int row, int kq) {
+  uint32_t* p = tile + row * kRowDwords + 4 * kq;
+  p[0] = r.x; p[1] = r.y; p[2] = r.z; p[3] = r.w;
 }
 
 __device__ __forceinline__ u32x4 read_operand(const uint32_t* tile, int row, int dword0) {
@@ -108,9 +96,21 @@ __device__ __forceinline__ u32x4 read_operand(const uint32_t* tile, int row, int
   return v;
 }
 
+// One k-tile of both operands in a thread's registers.
+struct Staged {
+  uint4 a[4];
+  uint4 b[2];
+};
+
+// Is the 256 x 128 tile that holds element (row, col) left out of a symmetric product?
+__device__ __forceinline__ bool tile_skipped(int row, int col) {
+  return kTileN * (col / kTileN + 1) <= kTileM * (row / kTileM);
+}
+
 template <typename T, bool A_KMAJOR>
-__global__ __launch_bounds__(256) void contraction_kernel(ContractionArgs a) {
-  __shared__ uint32_t lds[2][2][kTileDwords];   // [buffer][A | B]
+__global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) {
+  __shared__ uint32_t lds_a[2][kTileDwordsA];
+  __shared__ uint32_t lds_b[2][kTileDwordsB];
 
   // workgroup -> tile: 32 consecutive workgroups of one XCD take one 4 x 8 patch of tiles
   const int xcd = blockIdx.x & 7;
@@ -121,17 +121,17 @@ __global__ __launch_bounds__(256) void contraction_kernel(ContractionArgs a) {
   const int tm = (patch / a.patches_n) * kPatchM + (within >> 3);
   const int tn = (patch % a.patches_n) * kPatchN + (within & 7);
   if (tm >= a.tiles_m || tn >= a.tiles_n) return;
-  if (a.symmetric && tn < tm) return;
-  const int m0 = tm * kTile, n0 = tn * kTile;
+  const int m0 = tm * kTileM, n0 = tn * kTileN;
+  if (a.symmetric && tile_skipped(m0, n0)) return;
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int g = (lane & 7) + 8 * (w & 1);
   const int kp = (lane >> 3) + 8 * (w >> 1);
-  const int wm = w >> 1, wn = w & 1;
+  const int wm = w >> 1, wn = w & 1;    // wave tile: rows wm * 128 .. + 127, columns wn * 64 .. + 63
 
-  float16v acc[2][2];
+  float16v acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -140,64 +140,78 @@ __global__ __launch_bounds__(256) void contraction_kernel(ContractionArgs a) {
   const int ktiles = (a.Kd + kKTile - 1) / kKTile;
   const int iters = ktiles * a.npairs;
 
-  auto fetch = [&](int it, Staged& sa, Staged& sb) {
+  auto fetch = [&](int it, Staged& st) {
     const int p = it / ktiles;
     const int k0 = (it - p * ktiles) * kKTile;
     const uint16_t* Ap = a.A + a.pa[p] * a.a_term_stride;
     const uint16_t* Bp = a.B + a.pb[p] * a.b_term_stride;
-    if (A_KMAJOR)
-      sa = load_kmajor(Ap, a.M, k0, a.Kd, m0, a.M, g, kp);
-    else
-      sa = load_kcontig(Ap, a.Kd, k0, a.Kd, m0, a.M, t);
-    sb = load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g, kp);
+    if (A_KMAJOR) {
+      load_kmajor(Ap, a.M, k0, a.Kd, m0, a.M, g, kp, st.a[0], st.a[1]);
+      load_kmajor(Ap, a.M, k0, a.Kd, m0, a.M, g + 16, kp, st.a[2], st.a[3]);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st.a[r] = load_kcontig(Ap, a.Kd, k0, a.Kd, m0, a.M, (t >> 2) + 64 * r, t & 3);
+    }
+    load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g, kp, st.b[0], st.b[1]);
   };
-  auto stash = [&](int buf, const Staged& sa, const Staged& sb) {
-    if (A_KMAJOR)
-      store_kmajor(lds[buf][0], sa, g, kp);
-    else
-      store_kcontig(lds[buf][0], sa, t);
-    store_kmajor(lds[buf][1], sb, g, kp);
+  auto stash = [&](int buf, const Staged& st) {
+    if (A_KMAJOR) {
+      store_kmajor(lds_a[buf], st.a[0], st.a[1], g, kp);
+      store_kmajor(lds_a[buf], st.a[2], st.a[3], g + 16, kp);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) store_kcontig(lds_a[buf], st.a[r], (t >> 2) + 64 * r, t & 3);
+    }
+    store_kmajor(lds_b[buf], st.b[0], st.b[1], g, kp);
   };
-
-  Staged sa, sb;
-  fetch(0, sa, sb);
-  stash(0, sa, sb);
-  __syncthreads();
-  for (int it = 0; it < iters; ++it) {
-    const int buf = it & 1;
-    const bool more = it + 1 < iters;
-    if (more) fetch(it + 1, sa, sb);
-    const uint32_t* At = lds[buf][0];
-    const uint32_t* Bt = lds[buf][1];
+  auto compute = [&](int buf) {
+    const uint32_t* At = lds_a[buf];
+    const uint32_t* Bt = lds_b[buf];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const int dw = s * 8 + (lane >> 5) * 4;
-      u32x4 av[2], bv[2];
+      u32x4 av[4], bv[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        av[i] = read_operand(At, wm * 64 + i * 32 + (lane & 31), dw);
-        bv[i] = read_operand(Bt, wn * 64 + i * 32 + (lane & 31), dw);
-      }
+      for (int i = 0; i < 4; ++i) av[i] = read_operand(At, wm * 128 + i * 32 + (lane & 31), dw);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < 2; ++j) bv[j] = read_operand(Bt, wn * 64 + j * 32 + (lane & 31), dw);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(av[i], bv[j], acc[i][j]);
     }
-    if (more) stash(buf ^ 1, sa, sb);
+  };
+
+  // Tile it is computed from LDS buffer it & 1 while the loads of tile it + 2 are in flight and tile
+  // it + 1 (loaded one step earlier) moves from registers to the other buffer: one barrier per tile.
+  Staged s0, s1;
+  fetch(0, s0);
+  stash(0, s0);
+  if (iters > 1) fetch(1, s1);
+  __syncthreads();
+  for (int it = 0; it < iters; it += 2) {
+    if (it + 2 < iters) fetch(it + 2, s0);
+    compute(0);
+    if (it + 1 < iters) stash(1, s1);
     __syncthreads();
+    if (it + 1 < iters) {
+      if (it + 3 < iters) fetch(it + 3, s1);
+      compute(1);
+      if (it + 2 < iters) stash(0, s0);
+      __syncthreads();
+    }
   }
 
   // accumulator register r of lane l: row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
-  const bool mirror = a.symmetric && tn != tm;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int n = n0 + wn * 64 + j * 32 + (lane & 31);
       if (n >= a.N) continue;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int mb = m0 + wm * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5);
+        const int mb = m0 + wm * 128 + i * 32 + 8 * r4 + 4 * (lane >> 5);
         float v[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[q] = acc[i][j][r4 * 4 + q] * a.post_scale;
@@ -214,7 +228,9 @@ __global__ __launch_bounds__(256) void contraction_kernel(ContractionArgs a) {
               *c = o;
               v[q] = o;
             }
-          if (mirror && mb < a.M) {        // M % 4 == 0: the four rows are valid together
+          // element (n, mb .. mb + 3) of a symmetric product, when the tile it falls in is not computed
+          // (M % 4 == 0 and mb % 4 == 0: the four are valid together and share a tile)
+          if (a.symmetric && mb < a.M && tile_skipped(n, mb)) {
             float4 o4 = make_float4(v[0], v[1], v[2], v[3]);
             *reinterpret_cast<float4*>(a.C32 + static_cast<long>(n) * a.N + mb) = o4;
           }
@@ -252,8 +268,8 @@ hipError_t launch_split_terms(const float* src, uint16_t* dst, long n, float pre
 }
 
 hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s) {
-  a.tiles_m = (a.M + kTile - 1) / kTile;
-  a.tiles_n = (a.N + kTile - 1) / kTile;
+  a.tiles_m = (a.M + kTileM - 1) / kTileM;
+  a.tiles_n = (a.N + kTileN - 1) / kTileN;
   a.patches_m = (a.tiles_m + kPatchM - 1) / kPatchM;
   a.patches_n = (a.tiles_n + kPatchN - 1) / kPatchN;
   const long patches = static_cast<long>(a.patches_m) * a.patches_n;
