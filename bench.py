@@ -471,9 +471,14 @@ def main():
         torch.cuda.synchronize()
         names = ["h1_stage", "qkv", "o", "h3_stage", "gu", "down"]
         stage_us = {n: 0.0 for n in names}
+        step_us = []
         for es in evs:
             for k, n in enumerate(names):
                 stage_us[n] += es[k].elapsed_time(es[k + 1]) * 1e3 / n_ev
+            step_us.append(es[0].elapsed_time(es[6]) * 1e3)
+        step_us.sort()
+        step_pct = {"p10": round(step_us[len(step_us) // 10], 2), "median": round(step_us[len(step_us) // 2], 2),
+                    "p90": round(step_us[(len(step_us) * 9) // 10], 2), "n": len(step_us)}
         if B == 1:
             sparse_launch_us = (stage_us["qkv"] + stage_us["o"] + stage_us["gu"] + stage_us["down"]) / 4.0
     # rows a launch has to read: the kept rows at batch 1, the union of the tokens' kept rows otherwise
@@ -598,6 +603,7 @@ def main():
             "layer_GBs_on_all_bytes": round(all_bytes_layer / (graph_us * 1e-6) / 1e9, 1),
             "sparse_projections_us_per_layer": round(sparse_proj_layer_us, 2),
             "stage_us_in_layer": None if stage_us is None else {k: round(v, 2) for k, v in stage_us.items()},
+            "eager_step_us_percentiles": step_pct,      # per-step HIP events (first to last kernel of a step)
             "standalone_sparse_gemv_us_per_launch": round(standalone_launch_us, 3),
             "per_projection": per_proj,
             "dense_gemv_us_per_layer": round(dense_layer_us, 2),

@@ -305,17 +305,21 @@ class Layer:
     """Operands of one decoder layer, already widened to fp64.
     Wqkv [d, d_q+2d_kv] and Wgu [d, 2 d_ff] are folded with Q on the input side when the
     caller rotates (h1, h3); Wo [d_q, d] and Wdown [d_ff, d] meet unrotated h2, h4 (Q = I).
-    Q_attn / Q_mlp / adapter may be None.  rms_eps < 0 disables the pre-norm."""
+    Q_attn / Q_mlp / adapter may be None.  rms_eps < 0 disables the pre-norm.
+    shortcut_attn / shortcut_mlp (None = identity) are residual adapters on the two shortcuts
+    (Sec. 4.2; block-level rotations use one per block, Sec. 5.4): the stream that skips a block is
+    taken from the block's input basis to the basis its output projection was folded with."""
 
     def __init__(self, d, d_q, d_kv, d_ff, head_dim, K1, K2, K3, K4, Wqkv, Wo, Wgu, Wdown,
                  Q_attn=None, Q_mlp=None, adapter=None, rms_attn=None, rms_mlp=None,
-                 rms_eps=-1.0, dtype="f16"):
+                 rms_eps=-1.0, dtype="f16", shortcut_attn=None, shortcut_mlp=None):
         self.d, self.d_q, self.d_kv, self.d_ff, self.head_dim = d, d_q, d_kv, d_ff, head_dim
         self.K1, self.K2, self.K3, self.K4 = K1, K2, K3, K4
         self.Wqkv, self.Wo, self.Wgu, self.Wdown = Wqkv, Wo, Wgu, Wdown
         self.Q_attn, self.Q_mlp, self.adapter = Q_attn, Q_mlp, adapter
         self.rms_attn, self.rms_mlp, self.rms_eps = rms_attn, rms_mlp, rms_eps
         self.dtype = dtype
+        self.shortcut_attn, self.shortcut_mlp = shortcut_attn, shortcut_mlp
 
 
 def block_input(x: np.ndarray, Q, rms_scale, rms_eps: float, dtype) -> np.ndarray:
@@ -340,9 +344,15 @@ def stage_qkv(L: Layer, h1, idx1, dtype):
     return round16(sparse_project_gather(h1, idx1, L.Wqkv), dtype)
 
 
+def stage_shortcut(x, A, dtype):
+    """The residual shortcut around a block: the stream itself, or x (Q_in^T Q_out) through a
+    residual adapter (Sec. 4.2), one storage rounding."""
+    return np.asarray(x, np.float64) if A is None else round16(rotate(x, A), dtype)
+
+
 def stage_attn_out(L: Layer, x, h2, idx2, dtype):
     o = round16(sparse_project_gather(h2, idx2, L.Wo), dtype)
-    return o, round16(x + o, dtype)
+    return o, round16(stage_shortcut(x, L.shortcut_attn, dtype) + o, dtype)
 
 
 def stage_gate_up(L: Layer, h3, idx3, dtype):
@@ -355,7 +365,7 @@ def stage_h4(L: Layer, gu, dtype):
 
 def stage_down(L: Layer, x1, h4, idx4, dtype):
     dn = round16(sparse_project_gather(h4, idx4, L.Wdown), dtype)
-    return dn, round16(x1 + dn, dtype)
+    return dn, round16(stage_shortcut(x1, L.shortcut_mlp, dtype) + dn, dtype)
 
 
 def stage_adapter(L: Layer, x2, dtype):
@@ -384,4 +394,5 @@ def layer_forward(L: Layer, x: np.ndarray, rounded: bool = True) -> dict:
     down, x2 = stage_down(L, x1, h4, idx4, dt)
     x_out = stage_adapter(L, x2, dt)
     return dict(h1=h1, idx1=idx1, qkv=qkv, h2=h2, idx2=idx2, o=o, x1=x1, h3=h3, idx3=idx3,
-                gu=gu, h4=h4, idx4=idx4, down=down, x2=x2, x_out=x_out)
+                gu=gu, h4=h4, idx4=idx4, down=down, x2=x2, x_out=x_out,
+                s1=stage_shortcut(x, L.shortcut_attn, dt), s2=stage_shortcut(x1, L.shortcut_mlp, dt))

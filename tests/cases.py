@@ -145,6 +145,56 @@ def build_folded_stack(shape: synth.LayerShape, n_layers: int, p: float, seed: i
     return layers, bits, Qs, Ws, src
 
 
+def build_shortcut_stack(shape: synth.LayerShape, n_layers: int, p: float, seed: int, n_cal: int,
+                         store: bool = True):
+    """n_layers decoder layers with block-level rotations and residual adapters on the shortcuts
+    (Sec. 4.2, Sec. 5.4 "block-level"): layer l's attention block works in the basis Qa_l, its MLP
+    block in Qm_l.  q|k|v carry Qa_l^T and gate|up Qm_l^T on the input side; o carries Qm_l and down
+    carries Qa_{l+1} on the output side; the stream that skips the attention block goes through
+    Qa_l^T Qm_l, the one that skips the MLP block through Qm_l^T Qa_{l+1}.  The stack takes the
+    stream in the basis Qa_0 and returns it in the model's own basis (Qa_L = I).  Bases come from PCA
+    of the (normed) block inputs reached by pushing calibration tokens through the dense fp64 stack.
+    Returns (layers, bits, Qa list, dense weights, source)."""
+    dt = shape.dtype if store else None
+    src = synth.activation_source(shape.d, seed)
+    X = src.draw(n_cal, seed + 1)
+    Ws, Qa, Qm = [], [], []
+    for l in range(n_layers):
+        W = synth.layer_weights(shape, seed + 100 + 10 * l)
+        Ws.append(W)
+        Qa.append(O.pca_rotation(O.second_moment(O.rmsnorm(X, RMS_EPS)))[0])
+        X1 = _dense_attention_half(X, W, shape, True)
+        Qm.append(O.pca_rotation(O.second_moment(O.rmsnorm(X1, RMS_EPS)))[0])
+        X = dense_layer_reference(W, shape, X)
+    Qa.append(np.eye(shape.d))
+    Ks = (O.kept_count(shape.d, p), O.kept_count(shape.d_q, p),
+          O.kept_count(shape.d, p), O.kept_count(shape.d_ff, p))
+    layers, bits = [], []
+    for l in range(n_layers):
+        W = Ws[l]
+        ops = dict(
+            Wqkv=O.fold_input_side(Qa[l], np.concatenate([W["q"], W["k"], W["v"]], axis=1)),
+            Wo=O.fold_output_side(W["o"], Qm[l]),
+            Wgu=O.fold_input_side(Qm[l], np.concatenate([W["gate"], W["up"]], axis=1)),
+            Wdown=O.fold_output_side(W["down"], Qa[l + 1]),
+            shortcut_attn=O.residual_adapter(Qa[l], Qm[l]),
+            shortcut_mlp=O.residual_adapter(Qm[l], Qa[l + 1]))
+        b = {}
+        if store:
+            for k in list(ops):
+                b[k], v = _store(ops[k], dt)
+                ops[k] = v
+            ops["shortcut_attn"] = ops["shortcut_attn"].astype(np.float64)
+            ops["shortcut_mlp"] = ops["shortcut_mlp"].astype(np.float64)
+        b["Q_attn"] = b["Q_mlp"] = b["adapter"] = None
+        bits.append(b)
+        layers.append(O.Layer(shape.d, shape.d_q, shape.d_kv, shape.d_ff, shape.head_dim, *Ks,
+                              Wqkv=ops["Wqkv"], Wo=ops["Wo"], Wgu=ops["Wgu"], Wdown=ops["Wdown"],
+                              shortcut_attn=ops["shortcut_attn"], shortcut_mlp=ops["shortcut_mlp"],
+                              rms_eps=RMS_EPS, dtype=shape.dtype))
+    return layers, bits, Qa, Ws, src
+
+
 def dense_layer_reference(W: dict, shape: synth.LayerShape, X: np.ndarray, use_rms: bool = True) -> np.ndarray:
     """Textbook pre-norm decoder layer at context length 1 in fp64, no rotation, no sparsity:
     x1 = x + Attn(norm(x)) W_o with Attn = value head of the query head's group;

@@ -47,6 +47,39 @@ def test_folded_stack_with_adapters_full_K_equals_dense_stack():
         assert np.max(np.abs(xt - want[t])) < 1e-9 * np.max(np.abs(want[t]))
 
 
+def test_shortcut_adapter_stack_full_K_equals_dense_stack():
+    """Block-level rotations with a residual adapter on each shortcut (Sec. 4.2, Sec. 5.4): at full K
+    the stack, entered in the first block's basis, returns the dense stack's output."""
+    n_layers = 2
+    layers, _, Qa, Ws, src = cases.build_shortcut_stack(SMALL, n_layers, 0.4, seed=51, n_cal=512, store=False)
+    for L in layers:
+        for A in (L.shortcut_attn, L.shortcut_mlp):
+            assert np.max(np.abs(A.T @ A - np.eye(SMALL.d))) < 1e-10
+        assert L.Q_attn is None and L.Q_mlp is None and L.adapter is None      # every rotation is absorbed
+    X = src.draw(3, seed=9)
+    want = X
+    for W in Ws:
+        want = cases.dense_layer_reference(W, SMALL, want)
+    for t in range(3):
+        xt = O.rotate(X[t], Qa[0])
+        for L in layers:
+            _full_K(L)
+            r = O.layer_forward(L, xt, rounded=False)
+            # the shortcut values are the adapters applied to the block inputs
+            assert np.allclose(r["s1"], xt @ L.shortcut_attn, atol=1e-12)
+            assert np.allclose(r["s2"], r["x1"] @ L.shortcut_mlp, atol=1e-12)
+            xt = r["x_out"]
+        assert np.max(np.abs(xt - want[t])) < 1e-9 * np.max(np.abs(want[t]))
+    # and it is the same function as the stack with one adapter after each layer when both use the
+    # same per-layer basis: adapter on the shortcut + output-side fold == adapter after the add
+    rng = np.random.default_rng(3)
+    d = SMALL.d
+    Ql, Qn = synth.planted_basis(d, 71), synth.planted_basis(d, 72)
+    x1, y = rng.standard_normal(d), rng.standard_normal(d)             # y: block output in basis Ql
+    A = O.residual_adapter(Ql, Qn)
+    assert np.allclose((x1 + y) @ A, x1 @ A + y @ A, atol=1e-12)
+
+
 def test_sparse_layer_is_close_to_dense_and_keeps_exact_counts():
     case = cases.build_block_layer(SMALL, 0.25, seed=41, n_cal=512)
     L = case.layer
