@@ -27,12 +27,12 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script scaled by a 1 GiB copy (profiles/gemv_rows_llama2_7b_layer_b1_s40_hbm_traffic.txt).
-# Keyed by (config, batch, sparsity); other workloads have not been counted.
-MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4): 63.2e6}
+# Keyed by (config, batch, sparsity, form); other workloads have not been counted.
+MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4, "explicit"): 63.2e6}
 
 CONFIGS = {
     1: dict(shape="llama2-7b", workload="LLaMA2-7B-shaped decoder layer, fp16, batch 1, 40% sparsity, "
-                                        "explicit Q_attn/Q_mlp from PCA of 4096 synthetic calibration tokens",
+                                        "rotations Q_attn/Q_mlp from PCA of 4096 synthetic calibration tokens",
             n_cal=4096, latent="gauss"),
     2: dict(shape="llama3-8b", workload="LLaMA3-8B-shaped decoder layer (GQA), bf16", n_cal=4096, latent="gauss"),
     3: dict(shape="llama2-70b", workload="LLaMA2-70B-shaped decoder layer on one GPU, bf16", n_cal=8192,
@@ -301,6 +301,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy kernel) so that hardware counters "
                          "read under rocprofv3 can be scaled by a transfer of known size")
+    ap.add_argument("--form", default="shortcut", choices=["shortcut", "explicit"],
+                    help="how the layer's two rotations are executed: absorbed into the weights with a residual "
+                         "adapter on each shortcut (the deployed block-level form, default), or as explicit "
+                         "mat-vecs in front of q|k|v and gate|up")
     ap.add_argument("--offline", action="store_true",
                     help="time the offline contractions (second moment, folds, adapter) of the chosen "
                          "config's layer instead of the decode step; prints its own JSON line")
@@ -355,6 +359,10 @@ def main():
     ops0 = prepare.block_layer_operands(shape, W, Xc, td, dev)
     del W, Xc
     x = torch.as_tensor(src.draw(B, synth.seed_for(args.config, 5))).to(dev).to(td).contiguous()
+    x_explicit = x
+    shortcut_form = args.form == "shortcut"
+    if shortcut_form:      # the stream arrives in the attention block's basis
+        x = (x.double() @ ops0["Q_attn"].double()).to(td).contiguous()
     log(f"canonical layer prepared in {time.time() - t0:.1f}s")
 
     # ---- further weight sets: the folded weight of a Gaussian W under an orthogonal Q is again
@@ -365,14 +373,26 @@ def main():
     def gauss(r, c):
         return (torch.randn(r, c, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(td)
 
+    if shortcut_form:
+        ops0["Wo"], ops0["Wdown"] = ops0["Wo_out"], ops0["Wdown_out"]
     sets = [ops0]
     for _ in range(1, nsets):
         sets.append(dict(Wqkv=gauss(d, d_qkv), Wo=gauss(d_q, d), Wgu=gauss(d, 2 * d_ff), Wdown=gauss(d_ff, d),
-                         Q_attn=ops0["Q_attn"].clone(), Q_mlp=ops0["Q_mlp"].clone()))
-    layers = [api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, s["Wqkv"], s["Wo"], s["Wgu"],
-                        s["Wdown"], shape.dtype, Q_attn=s["Q_attn"], Q_mlp=s["Q_mlp"], rms_eps=prepare.RMS_EPS)
-              for s in sets]
-    ws = api.Workspace(layers[0].workspace_bytes(B))
+                         Q_attn=ops0["Q_attn"].clone(), Q_mlp=ops0["Q_mlp"].clone(),
+                         shortcut_attn=ops0["shortcut_attn"].clone(), shortcut_mlp=ops0["shortcut_mlp"].clone()))
+
+    def make_layer(s, form_shortcut):
+        if form_shortcut:
+            return api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, s["Wqkv"], s["Wo"], s["Wgu"],
+                             s["Wdown"], shape.dtype, rms_eps=prepare.RMS_EPS, shortcut_attn=s["shortcut_attn"],
+                             shortcut_mlp=s["shortcut_mlp"])
+        return api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, s["Wqkv"], s["Wo"], s["Wgu"],
+                         s["Wdown"], shape.dtype, Q_attn=s["Q_attn"], Q_mlp=s["Q_mlp"], rms_eps=prepare.RMS_EPS)
+
+    layers = [make_layer(s, shortcut_form) for s in sets]
+    # the other form on the same weight sets (timing only: the weights are random either way)
+    layers_other = [make_layer(s, not shortcut_form) for s in sets]
+    ws = api.Workspace(max(layers[0].workspace_bytes(B), layers_other[0].workspace_bytes(B)))
     out = torch.zeros_like(x)
     trace = layers[0].trace_buffers(B)
 
@@ -423,6 +443,22 @@ def main():
     graph_s = time.perf_counter() - t0
     graph_steps = replays * nsets
     graph_us = graph_s / graph_steps * 1e6
+
+    x_other = x_explicit if shortcut_form else (x.double() @ ops0["Q_attn"].double()).to(td).contiguous()
+
+    def all_layers_other():
+        for L in layers_other:
+            api.layer_forward(L, x_other, out, ws)
+
+    g_other = capture(all_layers_other)
+    for _ in range(max(1, args.warmup // nsets)):
+        g_other.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        g_other.replay()
+    torch.cuda.synchronize()
+    other_us = (time.perf_counter() - t0) / graph_steps * 1e6
 
     # ---- the dominant kernel alone: the four column-sparse projections of a layer on real
     # activations / index sets (taken from a traced run of set 0), HIP events on the launch stream
@@ -485,6 +521,9 @@ def main():
     U = [int(torch.unique(trace[n]).numel()) for n in ("idx1", "idx2", "idx3", "idx4")]
     sel_bytes_layer = 2 * (U[0] * d_qkv + U[1] * d + U[2] * 2 * d_ff + U[3] * d)
     sel_bytes_launch = sel_bytes_layer / 4.0
+    if B == 1 and shortcut_form:
+        # two of the four launches also stream a d x d residual adapter each: bytes the kernel must move
+        sel_bytes_launch = (sel_bytes_layer + 2 * 2 * d * d) / 4.0
     achieved_gbs = sel_bytes_launch / (sparse_launch_us * 1e-6) / 1e9
 
     per_proj = {}
@@ -531,7 +570,7 @@ def main():
         torch.cuda.synchronize()
         blas_layer_us = e0.elapsed_time(e1) * 1e3 / (reps * nsets)
     del lin_w
-    sparse_proj_layer_us = sparse_launch_us * 4
+    sparse_proj_layer_us = standalone_launch_us * 4      # the 4 projections with given indices, nothing else
     best_dense = min(dense_layer_us, blas_layer_us)
 
     # ---- CPU baseline: the fp64 oracle's layer on the host cores, bounded sample
@@ -547,9 +586,11 @@ def main():
             return O.decode16(bits(t), shape.dtype).astype(np.float32)
 
         s0 = sets[0]
+        rot = (dict(shortcut_attn=vals(s0["shortcut_attn"]).astype(np.float64),
+                    shortcut_mlp=vals(s0["shortcut_mlp"]).astype(np.float64)) if shortcut_form else
+               dict(Q_attn=vals(s0["Q_attn"]).astype(np.float64), Q_mlp=vals(s0["Q_mlp"]).astype(np.float64)))
         OL = O.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, Wqkv=vals(s0["Wqkv"]), Wo=vals(s0["Wo"]),
-                     Wgu=vals(s0["Wgu"]), Wdown=vals(s0["Wdown"]), Q_attn=vals(s0["Q_attn"]).astype(np.float64),
-                     Q_mlp=vals(s0["Q_mlp"]).astype(np.float64), rms_eps=prepare.RMS_EPS, dtype=shape.dtype)
+                     Wgu=vals(s0["Wgu"]), Wdown=vals(s0["Wdown"]), rms_eps=prepare.RMS_EPS, dtype=shape.dtype, **rot)
         xs = O.decode16(bits(x), shape.dtype)
         t0 = time.perf_counter()
         r = O.layer_forward(OL, xs[0])
@@ -583,19 +624,27 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["workload"] if args.config == 1 and p == 0.4 and B == 1 and args.alpha == "1.0,1.0"
                    else f"{cfg['workload']}; batch {B}; sparsity {p}; alpha1,alpha3 = {args.alpha}",
+                   "form": ("rotations absorbed into the weights, residual adapters Q_attn^T Q_mlp and Q_mlp^T Q_attn "
+                            "on the two shortcuts (each shares the launch of its block's first projection at batch 1)"
+                            if shortcut_form else "explicit rotation mat-vecs in front of q|k|v and gate|up"),
                    "shape": shape.name, "batch": B, "sparsity": p, "K": [K1, K2, K3, K4], "union_rows": U,
                    "weight_sets": nsets,
                    "launch": "one HIP graph of larosa_layer_forward per weight set"},
         "roofline": {"bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, B, p)) if args.alpha == "1.0,1.0" else None,
-                     "kernel": ("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step, "
-                                "timed by HIP events recorded inside larosa_layer_forward" if B == 1 else
-                                "skinny_fma/mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
+                     "traffic": (MEASURED_TRAFFIC_BYTES.get((args.config, B, p, args.form))
+                                 if args.alpha == "1.0,1.0" else None),
+                     "kernel": (("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step "
+                                 + ("(two of them carry a residual adapter in the same launch; its bytes are counted), "
+                                    if shortcut_form else ", ") +
+                                 "timed by HIP events recorded inside larosa_layer_forward") if B == 1 else
+                                "skinny_mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
                      "bytes_per_launch": sel_bytes_launch, "us_per_launch": round(sparse_launch_us, 3)},
         "cpu_baseline": cpu,
         "extra": {
             "eager_us_per_layer": round(eager_us, 2),
+            ("explicit_rotation_form_us_per_layer" if shortcut_form else "shortcut_form_us_per_layer"):
+                round(other_us, 2),
             "graph_us_per_layer": round(graph_us, 2),
             "tokens_per_s_32_layers": round(1e6 / (graph_us * 32), 1),
             "selected_row_bytes_per_layer": sel_bytes_layer,

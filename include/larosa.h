@@ -113,14 +113,23 @@ typedef struct {
   int attn_mode;              /* 0: context-length-1 attention (softmax over one key = 1, so each query
                                     head outputs the value head of its group).  No other mode yet. */
   larosa_dtype dtype;
+  /* Residual adapters on the two shortcuts (Sec. 4.2; with block-level rotations, Sec. 5.4, there is
+   * one per block), each [d,d] or NULL = identity: the stream that skips the attention block is taken
+   * through shortcut_attn (Q_attn^T Q_mlp when Wo was folded with Q_mlp on its output side), the one
+   * that skips the MLP block through shortcut_mlp (Q_mlp^T Q_next with Wdown folded with Q_next).
+   * They depend only on the block's input, so they run beside the block's first projection. */
+  const void* shortcut_attn;
+  const void* shortcut_mlp;
 } larosa_layer;
 
 /* Optional copies of every stage (device pointers, each nullable), for stage-by-stage checks:
  * h1 [B,d]; idx1 [B,K1]; qkv [B,d_q+2d_kv]; h2 [B,d_q]; idx2 [B,K2]; o [B,d]; x1 [B,d];
- * h3 [B,d]; idx3 [B,K3]; gu [B,2d_ff]; h4 [B,d_ff]; idx4 [B,K4]; down [B,d]; x2 [B,d]. */
+ * h3 [B,d]; idx3 [B,K3]; gu [B,2d_ff]; h4 [B,d_ff]; idx4 [B,K4]; down [B,d]; x2 [B,d];
+ * s1, s2 [B,d]: the shortcut values (written only when the layer has that shortcut adapter). */
 typedef struct {
   void *h1, *qkv, *h2, *o, *x1, *h3, *gu, *h4, *down, *x2;
   int32_t *idx1, *idx2, *idx3, *idx4;
+  void *s1, *s2;
   /* Optional caller-created hipEvent_t handles (each nullable), recorded on `stream` at the stage
    * boundaries so a caller can time the stages of one call: [0] on entry, [1] after the h1 stage
    * (rotation / pre-norm), [2] after q|k|v, [3] after o, [4] after the h3 stage, [5] after gate|up,
@@ -133,9 +142,10 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B);
 
 /* x [B,d] -> x_out [B,d]:
  *   h1 = R(norm(x) Q_attn); qkv = R(S_K1(h1) Wqkv); h2 = attention core of qkv;
- *   o = R(S_K2(h2) Wo); x1 = R(x + o); h3 = R(norm(x1) Q_mlp); gu = R(S_K3(h3) Wgu);
- *   h4 = R(SiLU(gate) * up); down = R(S_K4(h4) Wdown); x2 = R(x1 + down);
- *   x_out = R(x2 adapter) or x2.         R = one rounding to the layer dtype.
+ *   o = R(S_K2(h2) Wo); x1 = R(s1 + o); h3 = R(norm(x1) Q_mlp); gu = R(S_K3(h3) Wgu);
+ *   h4 = R(SiLU(gate) * up); down = R(S_K4(h4) Wdown); x2 = R(s2 + down);
+ *   x_out = R(x2 adapter) or x2;  s1 = R(x shortcut_attn) or x;  s2 = R(x1 shortcut_mlp) or x1.
+ *   R = one rounding to the layer dtype.
  * trace may be NULL.  x_out must not alias x. */
 int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int B,
                          const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
@@ -209,7 +219,8 @@ int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype
  * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
  * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,
  * 2: 4), key 3 = decoder layer with the Top-K fused into the projection kernels (1, default) or
- * as separate kernels (0), key 4 = row-waves per workgroup of that fused kernel (8 or 16).
+ * as separate kernels (0), key 4 = row-waves per workgroup of that fused kernel (8 or 16),
+ * key 5 / key 6 = workgroups of a projection / of the shortcut adapter that shares its launch.
  * Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 

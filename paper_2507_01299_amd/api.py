@@ -36,10 +36,12 @@ class _Layer(ctypes.Structure):
         ("Q_attn", ctypes.c_void_p), ("Q_mlp", ctypes.c_void_p), ("adapter", ctypes.c_void_p),
         ("rms_attn", ctypes.c_void_p), ("rms_mlp", ctypes.c_void_p),
         ("rms_eps", ctypes.c_float), ("attn_mode", ctypes.c_int), ("dtype", ctypes.c_int),
+        ("shortcut_attn", ctypes.c_void_p), ("shortcut_mlp", ctypes.c_void_p),
     ]
 
 
-TRACE_FIELDS = ("h1", "qkv", "h2", "o", "x1", "h3", "gu", "h4", "down", "x2", "idx1", "idx2", "idx3", "idx4")
+TRACE_FIELDS = ("h1", "qkv", "h2", "o", "x1", "h3", "gu", "h4", "down", "x2", "idx1", "idx2", "idx3", "idx4",
+                "s1", "s2")
 
 
 class _Trace(ctypes.Structure):
@@ -245,14 +247,18 @@ class Layer:
     """Holds the device tensors of one decoder layer and the matching C struct."""
 
     def __init__(self, d, d_q, d_kv, d_ff, head_dim, K1, K2, K3, K4, Wqkv, Wo, Wgu, Wdown, dtype,
-                 Q_attn=None, Q_mlp=None, adapter=None, rms_attn=None, rms_mlp=None, rms_eps=-1.0, attn_mode=0):
+                 Q_attn=None, Q_mlp=None, adapter=None, rms_attn=None, rms_mlp=None, rms_eps=-1.0, attn_mode=0,
+                 shortcut_attn=None, shortcut_mlp=None):
         self.tensors = dict(Wqkv=Wqkv, Wo=Wo, Wgu=Wgu, Wdown=Wdown, Q_attn=Q_attn, Q_mlp=Q_mlp,
-                            adapter=adapter, rms_attn=rms_attn, rms_mlp=rms_mlp)   # keep alive
+                            adapter=adapter, rms_attn=rms_attn, rms_mlp=rms_mlp, shortcut_attn=shortcut_attn,
+                            shortcut_mlp=shortcut_mlp)   # keep alive
         self.dtype = dtype_code(dtype)
         self.c = _Layer(d, d_q, d_kv, d_ff, head_dim, K1, K2, K3, K4,
                         *[None if t is None else t.data_ptr() for t in
                           (Wqkv, Wo, Wgu, Wdown, Q_attn, Q_mlp, adapter, rms_attn, rms_mlp)],
-                        float(rms_eps), int(attn_mode), self.dtype)
+                        float(rms_eps), int(attn_mode), self.dtype,
+                        None if shortcut_attn is None else shortcut_attn.data_ptr(),
+                        None if shortcut_mlp is None else shortcut_mlp.data_ptr())
 
     def workspace_bytes(self, B: int) -> int:
         return lib().larosa_layer_workspace_bytes(ctypes.byref(self.c), B)
@@ -261,6 +267,10 @@ class Layer:
         c, td = self.c, torch_dtype(self.dtype)
         w = dict(h1=c.d, qkv=c.d_q + 2 * c.d_kv, h2=c.d_q, o=c.d, x1=c.d, h3=c.d, gu=2 * c.d_ff, h4=c.d_ff,
                  down=c.d, x2=c.d)
+        if c.shortcut_attn:
+            w["s1"] = c.d
+        if c.shortcut_mlp:
+            w["s2"] = c.d
         out = {k: torch.zeros(B, v, dtype=td, device=device) for k, v in w.items()}
         for k, K in (("idx1", c.K1), ("idx2", c.K2), ("idx3", c.K3), ("idx4", c.K4)):
             out[k] = torch.full((B, K), -1, dtype=torch.int32, device=device)

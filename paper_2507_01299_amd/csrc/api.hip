@@ -82,17 +82,34 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   return launch_gemv(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
-// One launch of the projection kernel with the Top-K prologue.
+// One launch of the projection kernel with the Top-K prologue, optionally with a dense side job
+// (a.side.W != nullptr: y_side = x_side * W_side over all rows) in the same grid.
 int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
-  const GemvPlan p = plan_fused(a.g.d_out, a.g.K);
-  if (static_cast<size_t>(a.g.B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
-  const size_t need = kCounterBytes + static_cast<size_t>(a.g.B) * p.partial_floats * sizeof(float);
-  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  const bool side = a.side.W != nullptr;
+  const GemvPlan p = plan_fused(a.g.d_out, a.g.K, side ? tuning().side_main_g : 0);
+  size_t slots = static_cast<size_t>(a.g.B) * p.nstrips;
+  size_t pfloats = static_cast<size_t>(a.g.B) * p.partial_floats;
+  unsigned* counters = static_cast<unsigned*>(ws);
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  a.side_G = 0;
+  if (side) {
+    const GemvPlan ps = plan_gemv(a.side.d_out, a.side.K, tuning().side_g);
+    a.side.chunk = ps.chunk;
+    a.side.G = ps.G;
+    a.side.nstrips = ps.nstrips;
+    a.side.counters = counters + slots * kCounterStride;
+    a.side.partial = partial + pfloats;
+    a.side_G = ps.G;
+    slots += static_cast<size_t>(a.side.B) * ps.nstrips;
+    pfloats += static_cast<size_t>(a.side.B) * ps.partial_floats;
+  }
+  if (slots > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  if (!ws || !aligned(ws, 256) || ws_bytes < kCounterBytes + pfloats * sizeof(float)) return LAROSA_EWORKSPACE;
   a.g.chunk = p.chunk;
   a.g.G = p.G;
   a.g.nstrips = p.nstrips;
-  a.g.counters = static_cast<unsigned*>(ws);
-  a.g.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+  a.g.counters = counters;
+  a.g.partial = partial;
   return launch_fused(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
@@ -222,7 +239,8 @@ static int check_layer(const larosa_layer* L, int B) {
       L->K4 > L->d_ff)
     return LAROSA_EINVAL;
   if (!L->Wqkv || !L->Wo || !L->Wgu || !L->Wdown) return LAROSA_EINVAL;
-  const void* ptrs[] = {L->Wqkv, L->Wo, L->Wgu, L->Wdown, L->Q_attn, L->Q_mlp, L->adapter, L->rms_attn, L->rms_mlp};
+  const void* ptrs[] = {L->Wqkv, L->Wo, L->Wgu, L->Wdown, L->Q_attn, L->Q_mlp, L->adapter, L->rms_attn, L->rms_mlp,
+                        L->shortcut_attn, L->shortcut_mlp};
   for (const void* p : ptrs)
     if (p && !aligned(p, 16)) return LAROSA_EINVAL;
   if (L->attn_mode != 0) return LAROSA_EUNSUPPORTED;
@@ -240,6 +258,16 @@ static size_t layer_gemv_ws(const larosa_layer* L, int B) {
   for (const GemvPlan& p : plans) {
     const size_t need = round_up(kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float), 256);
     if (need > s) s = need;
+  }
+  if (L->shortcut_attn || L->shortcut_mlp) {   // a projection and its shortcut adapter in one launch
+    const GemvPlan side = plan_gemv(L->d, L->d, tuning().side_g);
+    const GemvPlan mains[] = {plan_fused(L->d_q + 2 * L->d_kv, L->K1, tuning().side_main_g),
+                              plan_fused(2 * L->d_ff, L->K3, tuning().side_main_g)};
+    for (const GemvPlan& p : mains) {
+      const size_t need = round_up(
+          kCounterBytes + static_cast<size_t>(B) * (p.partial_floats + side.partial_floats) * sizeof(float), 256);
+      if (need > s) s = need;
+    }
   }
   if (B > 1) {
     const bool cs = L->rms_attn || L->rms_mlp;
@@ -263,7 +291,7 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
   size_t s = layer_gemv_ws(L, B);
   const size_t widths[] = {(size_t)L->d, (size_t)(L->d_q + 2 * L->d_kv), (size_t)L->d_q, (size_t)L->d,
                            (size_t)L->d, (size_t)L->d, (size_t)(2 * L->d_ff), (size_t)L->d_ff,
-                           (size_t)L->d, (size_t)L->d};
+                           (size_t)L->d, (size_t)L->d, (size_t)L->d, (size_t)L->d};
   for (size_t w : widths) s += round_up(Bz * w * E, 256) + 256;
   const int Ks[] = {L->K1, L->K2, L->K3, L->K4};
   for (int k : Ks) s += round_up(Bz * k * sizeof(int32_t), 256) + 256;
@@ -303,6 +331,8 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   uint16_t* h4 = buf16(T.h4, d_ff);
   uint16_t* down = buf16(T.down, d);
   uint16_t* x2 = L->adapter ? buf16(T.x2, d) : static_cast<uint16_t*>(x_out);
+  uint16_t* s1 = L->shortcut_attn ? buf16(T.s1, d) : nullptr;
+  uint16_t* s2 = L->shortcut_mlp ? buf16(T.s2, d) : nullptr;
   int32_t* idx1 = bufidx(T.idx1, L->K1);
   int32_t* idx2 = bufidx(T.idx2, L->K2);
   int32_t* idx3 = bufidx(T.idx3, L->K3);
@@ -353,6 +383,21 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
                  : LAROSA_EHIP;
     return launch_copy_u16(src, dst, Bz * d, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
   };
+  // residual adapter on a shortcut as a launch of its own: dst = R(src A)
+  auto shortcut = [&](const uint16_t* src, const void* A, uint16_t* dst) -> int {
+    if (B > 1) {
+      BatchArgs a{};
+      a.W = static_cast<const uint16_t*>(A);
+      a.C = src; a.y = dst;
+      a.d_in = d; a.d_out = d; a.B = B;
+      return run_batched(a, bf, ws, gws, st);
+    }
+    GemvArgs a{};
+    a.W = static_cast<const uint16_t*>(A);
+    a.h = src; a.y = dst;
+    a.d_in = d; a.d_out = d; a.K = d; a.B = B;
+    return run_gemv(a, bf, ws, gws, st);
+  };
   auto sparse = [&](const void* W, const uint16_t* h, const int32_t* idx, uint16_t* y, int d_in, int d_out, int K,
                     const uint16_t* residual, uint16_t* y_pre) -> int {
     GemvArgs a{};
@@ -379,6 +424,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       a.residual = residual; a.y_pre = y_pre;
       return run_batched(a, bf, ws, gws, st);
     };
+    if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
     LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
     mark(1);
     LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, masked, st));
@@ -391,8 +437,9 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       sc.group = (d_q / L->head_dim) / (d_kv / L->head_dim);
       LAROSA_HIP(launch_topk_from(sc, B, d_q, L->K2, idx2, masked, bf, st));
     }
-    LAROSA_TRY(project(L->Wo, d_q, d, x1, x, o));
+    LAROSA_TRY(project(L->Wo, d_q, d, x1, s1 ? s1 : x, o));
     mark(3);
+    if (s2) LAROSA_TRY(shortcut(x1, L->shortcut_mlp, s2));
     LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
     mark(4);
     LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, masked, st));
@@ -403,14 +450,20 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
       LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, masked, bf, st));
     }
-    LAROSA_TRY(project(L->Wdown, d_ff, d, x2, x1, down));
+    LAROSA_TRY(project(L->Wdown, d_ff, d, x2, s2 ? s2 : x1, down));
     mark(6);
   } else if (tuning().fused) {
     // Top-K fused into the projections: 4 projection kernels (+ one rotation each when Q is given)
     auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
                      const uint16_t* residual, uint16_t* y_pre, uint16_t* h_out, int32_t* idx_out,
-                     const void* nscale) -> int {
+                     const void* nscale, const void* sideA = nullptr, const uint16_t* side_x = nullptr,
+                     uint16_t* side_y = nullptr) -> int {
       FusedArgs a{};
+      if (sideA) {
+        a.side.W = static_cast<const uint16_t*>(sideA);
+        a.side.h = side_x; a.side.y = side_y;
+        a.side.d_in = d; a.side.d_out = d; a.side.K = d; a.side.B = B;
+      }
       a.g.W = static_cast<const uint16_t*>(W);
       a.g.y = y;
       a.g.d_in = d_in; a.g.d_out = d_out; a.g.K = K; a.g.B = B;
@@ -422,37 +475,40 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       a.h_out = h_out; a.idx_out = idx_out;
       return run_fused(a, bf, ws, gws, st);
     };
+    // the block's first projection; its shortcut adapter (sc: A, dst) shares the launch
     auto first = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* h, void* h_traced, const void* W,
-                     uint16_t* y, int d_out, int K, int32_t* idx_traced) -> int {
+                     uint16_t* y, int d_out, int K, int32_t* idx_traced, const void* scA, uint16_t* sc_dst) -> int {
       if (Q) {
         if (int rc = block_input(src, Q, scale, h)) return rc;
         mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
-        return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr);
+        return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr, scA, src,
+                     sc_dst);
       }
       mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
       return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
-                   static_cast<uint16_t*>(h_traced), idx_traced, scale);
+                   static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst);
     };
-    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1));
+    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1, L->shortcut_attn, s1));
     mark(2);
-    LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, x, static_cast<uint16_t*>(T.o),
+    LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, s1 ? s1 : x, static_cast<uint16_t*>(T.o),
                      static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
     mark(3);
-    LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3));
+    LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2));
     mark(5);
     if (d_ff <= kFusedMaxWidth) {
-      LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, x1, static_cast<uint16_t*>(T.down),
+      LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
                        static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
     } else {
       // a wide intermediate vector makes the per-workgroup selection too long: select once instead
       TopkSource sc{};
       sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
       LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, nullptr, bf, st));
-      LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+      LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, s2 ? s2 : x1, down));
     }
     mark(6);
   } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
+  if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
   LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
   mark(1);
   LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, nullptr, st));
@@ -460,9 +516,10 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   mark(2);
   LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
   LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, nullptr, st));
-  LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, x, o));
+  LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, s1 ? s1 : x, o));
   mark(3);
   // MLP block: h3 -> gate|up -> h4 -> down -> + residual
+  if (s2) LAROSA_TRY(shortcut(x1, L->shortcut_mlp, s2));
   LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
   mark(4);
   LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, nullptr, st));
@@ -470,7 +527,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   mark(5);
   LAROSA_HIP(launch_silu_mul(gu, h4, B, d_ff, bf, st));
   LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
-  LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, x1, down));
+  LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, s2 ? s2 : x1, down));
   mark(6);
   }
   // residual adapter
@@ -681,6 +738,14 @@ int larosa_set_tuning(int key, int value) {
     case 4:
       if (value != 8 && value != 16) return LAROSA_EINVAL;
       tuning().fused_rw = value;
+      return LAROSA_OK;
+    case 5:
+      if (value < 8 || value > 2048) return LAROSA_EINVAL;
+      tuning().side_main_g = value;
+      return LAROSA_OK;
+    case 6:
+      if (value < 8 || value > 2048) return LAROSA_EINVAL;
+      tuning().side_g = value;
       return LAROSA_OK;
     default:
       return LAROSA_EINVAL;

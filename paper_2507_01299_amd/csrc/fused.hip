@@ -8,6 +8,11 @@
 // L2, so the redundant selection costs about a microsecond per workgroup and removes three
 // dependent kernels (copy/activation, Top-K, and the index/value gathers of the mat-vec) per
 // projection.  Workgroup 0 also writes the vector and the index list for callers that ask.
+//
+// A launch can carry a dense side job (FusedArgs::side): the residual adapter on the block's
+// shortcut, x (Q_in^T Q_out), needs only the block's input, so its workgroups stream their rows
+// while the projection's workgroups are still selecting, and the adapter leaves the layer's
+// critical path.
 #include "gemv_core.hpp"
 #include "topk_core.hpp"
 
@@ -28,7 +33,14 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   const int lane = tid & 63;
   const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = blockIdx.y;
-  const int g = blockIdx.x;
+  int g = blockIdx.x;
+  if (a.side_G > 0) {                     // uniform over the workgroup
+    if (g < a.side_G) {
+      gemv_rows_body<T, RW, false>(a.side, g, b, sh);
+      return;
+    }
+    g -= a.side_G;
+  }
   const int d_in = a.g.d_in;
   const int K = a.g.K;
   const int base = tid * E;
@@ -158,7 +170,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
 
 template <typename T, int RW>
 hipError_t launch_nv(const FusedArgs& a, hipStream_t st) {
-  dim3 grid(a.g.G, a.g.B), block(RW * 64);
+  dim3 grid(a.g.G + a.side_G, a.g.B), block(RW * 64);
   const int nv = (a.g.d_in + RW * 64 * 4 - 1) / (RW * 64 * 4);
 #define LAROSA_FUSED_CASE(N) \
   if (nv <= N) { hipLaunchKernelGGL((fused_topk_gemv_kernel<T, RW, N>), grid, block, 0, st, a); return hipGetLastError(); }
@@ -185,9 +197,9 @@ hipError_t launch_rw(const FusedArgs& a, hipStream_t st) {
 
 int fused_row_waves() { return tuning().fused_rw == 16 ? 16 : 8; }
 
-GemvPlan plan_fused(int d_out, int K) {
-  GemvPlan p = plan_gemv(d_out, K);
-  if (fused_row_waves() == 16 && tuning().g_target == 0 && p.G > 256) {
+GemvPlan plan_fused(int d_out, int K, int g_hint) {
+  GemvPlan p = plan_gemv(d_out, K, g_hint);
+  if (fused_row_waves() == 16 && tuning().g_target == 0 && g_hint == 0 && p.G > 256) {
     // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
     const long T = static_cast<long>(p.nstrips) * K;
     long G = 256 > p.nstrips ? 256 : p.nstrips;

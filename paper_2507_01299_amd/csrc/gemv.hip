@@ -16,42 +16,7 @@ namespace {
 template <typename T, int RW, bool INDEXED>
 __global__ __launch_bounds__(RW * 64) void gemv_rows_kernel(GemvArgs a) {
   __shared__ GemvShared<RW> sh;
-  const int lane = threadIdx.x & 63;
-  const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-  const int b = blockIdx.y;
-  const int g = blockIdx.x;
-  const int K = a.K;
-
-  GlobalRows<T, INDEXED> rows;
-  rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
-  rows.h = a.h + static_cast<size_t>(b) * a.d_in;
-  rows.coef_scale = a.coef_scale;
-  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
-
-  int f0 = g * a.chunk;
-  const int f1 = min(f0 + a.chunk, a.nstrips * K);
-  Segment sg{f0 / K, 0, 0};
-  sg.t0 = f0 - sg.s * K;
-  int seg_no = 0;
-  while (f0 < f1) {
-    sg.t1 = min(K, sg.t0 + (f1 - f0));
-    const int col = sg.s * kStripCols + lane * 8;
-    float acc[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-    // this wave's run of kept rows
-    const int n = sg.t1 - sg.t0;
-    const int per = (n + RW - 1) / RW;
-    const int ra = sg.t0 + rw * per;
-    const int re = min(sg.t1, ra + per);
-    if (col < a.d_out) stream_rows<T>(a.W + col, a.d_out, rows, ra, re, acc);
-    reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
-                             rw);
-    f0 += sg.t1 - sg.t0;
-    sg.s += 1;
-    sg.t0 = 0;
-    seg_no += 1;
-  }
+  gemv_rows_body<T, RW, INDEXED>(a, blockIdx.x, blockIdx.y, sh);
 }
 
 template <typename T, int RW>
@@ -80,13 +45,13 @@ Tuning& tuning() {
   return t;
 }
 
-GemvPlan plan_gemv(int d_out, int K) {
+GemvPlan plan_gemv(int d_out, int K, int g_hint) {
   GemvPlan p;
   p.strip_cols = kStripCols;
   p.nstrips = (d_out + kStripCols - 1) / kStripCols;
   const long T = static_cast<long>(p.nstrips) * K;
   // 256 compute units: one workgroup each for small problems, two each otherwise
-  long G = tuning().g_target > 0 ? tuning().g_target : (T < 32768 ? 256 : 512);
+  long G = g_hint > 0 ? g_hint : tuning().g_target > 0 ? tuning().g_target : (T < 32768 ? 256 : 512);
   if (G > T / tuning().min_rows) G = T / tuning().min_rows;
   if (G < p.nstrips) G = p.nstrips;
   p.chunk = static_cast<int>((T + G - 1) / G);

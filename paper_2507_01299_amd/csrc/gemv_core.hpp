@@ -237,4 +237,44 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment
   __syncthreads();   // LDS is reused by a following segment
 }
 
+// The row-streaming mat-vec of workgroup g for token b: its share of the (strip, kept row) pairs,
+// at most two segments, each reduced and handed over by reduce_and_finish.
+template <typename T, int RW, bool INDEXED>
+__device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, GemvShared<RW>& sh) {
+  const int lane = threadIdx.x & 63;
+  const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const int K = a.K;
+
+  GlobalRows<T, INDEXED> rows;
+  rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
+  rows.h = a.h + static_cast<size_t>(b) * a.d_in;
+  rows.coef_scale = a.coef_scale;
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+
+  int f0 = g * a.chunk;
+  const int f1 = min(f0 + a.chunk, a.nstrips * K);
+  Segment sg{f0 / K, 0, 0};
+  sg.t0 = f0 - sg.s * K;
+  int seg_no = 0;
+  while (f0 < f1) {
+    sg.t1 = min(K, sg.t0 + (f1 - f0));
+    const int col = sg.s * kStripCols + lane * 8;
+    float acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+    // this wave's run of kept rows
+    const int n = sg.t1 - sg.t0;
+    const int per = (n + RW - 1) / RW;
+    const int ra = sg.t0 + rw * per;
+    const int re = min(sg.t1, ra + per);
+    if (col < a.d_out) stream_rows<T>(a.W + col, a.d_out, rows, ra, re, acc);
+    reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
+                             rw);
+    f0 += sg.t1 - sg.t0;
+    sg.s += 1;
+    sg.t0 = 0;
+    seg_no += 1;
+  }
+}
+
 }  // namespace larosa

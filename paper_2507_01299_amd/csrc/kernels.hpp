@@ -41,10 +41,13 @@ struct Tuning {
   int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
   int fused_rw = 8;           // row-waves of the fused kernel: 8 (two workgroups per CU) or 16 (one)
+  int side_main_g = 256;      // workgroups of a projection that shares its launch with a shortcut adapter
+  int side_g = 192;           // workgroups of that adapter (all of both jobs resident at once: 448 of 512 slots)
 };
 Tuning& tuning();
 
-GemvPlan plan_gemv(int d_out, int K);
+// g_hint > 0 asks for that many workgroups instead of the automatic choice
+GemvPlan plan_gemv(int d_out, int K, int g_hint = 0);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
 
 // The same mat-vec over 4-bit weights (w4.hip): g.W is unused; the row loop reads packed codes and
@@ -74,8 +77,13 @@ struct FusedArgs {
   float norm_eps;
   uint16_t* h_out;            // nullable: receives the input vector [B, d_in]
   int32_t* idx_out;           // nullable: receives the kept indices [B, K], ascending
+  // Optional dense mat-vec that shares the launch (a residual adapter on the block's shortcut: it
+  // depends only on the block's input, so its rows stream while the projection's workgroups select).
+  // Workgroups [0, side_G) of the grid run it; side.idx == nullptr, own counters and partials.
+  GemvArgs side;
+  int side_G;                 // 0: no side job
 };
-GemvPlan plan_fused(int d_out, int K);
+GemvPlan plan_fused(int d_out, int K, int g_hint = 0);
 int fused_row_waves();
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 

@@ -71,4 +71,10 @@ def block_layer_operands(shape, W: dict, Xcal, dtype: torch.dtype, device, use_r
     return dict(
         Wqkv=store(fold_input_side(Q_attn, Wqkv), dtype), Wo=store(Wd["o"], dtype),
         Wgu=store(fold_input_side(Q_mlp, Wgu), dtype), Wdown=store(Wd["down"], dtype),
-        Q_attn=store(Q_attn, dtype), Q_mlp=store(Q_mlp, dtype))
+        Q_attn=store(Q_attn, dtype), Q_mlp=store(Q_mlp, dtype),
+        # the same layer with every rotation absorbed (block-level form): o and down folded on the
+        # output side, residual adapters on the two shortcuts; the layer after it is taken to use
+        # the same attention basis, so its output is again a valid input
+        Wo_out=store(Wd["o"] @ Q_mlp, dtype), Wdown_out=store(Wd["down"] @ Q_attn, dtype),
+        shortcut_attn=store(residual_adapter(Q_attn, Q_mlp), dtype),
+        shortcut_mlp=store(residual_adapter(Q_mlp, Q_attn), dtype))

@@ -35,7 +35,9 @@ def device_layer(case, device="cuda:0"):
                      Wgu=to_dev(b["Wgu"], dt, device), Wdown=to_dev(b["Wdown"], dt, device), dtype=dt,
                      Q_attn=to_dev(b.get("Q_attn"), dt, device), Q_mlp=to_dev(b.get("Q_mlp"), dt, device),
                      adapter=to_dev(b.get("adapter"), dt, device), rms_attn=to_dev(b.get("rms_attn"), dt, device),
-                     rms_mlp=to_dev(b.get("rms_mlp"), dt, device), rms_eps=L.rms_eps)
+                     rms_mlp=to_dev(b.get("rms_mlp"), dt, device), rms_eps=L.rms_eps,
+                     shortcut_attn=to_dev(b.get("shortcut_attn"), dt, device),
+                     shortcut_mlp=to_dev(b.get("shortcut_mlp"), dt, device))
 
 
 def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.Tensor, tol=REL_L2_TOL) -> dict:
@@ -66,8 +68,12 @@ def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.
         h2 = O.decode16(g["h2"][b], dt)
         o, x1 = O.stage_attn_out(L, x, h2, g["idx2"][b], dt)
         close("o", g["o"][b], o)
-        # the residual add is checked from the GPU's own o
-        close("x1", g["x1"][b], O.round16(x + O.decode16(g["o"][b], dt), dt))
+        s1 = x
+        if L.shortcut_attn is not None:
+            close("s1", g["s1"][b], O.stage_shortcut(x, L.shortcut_attn, dt))
+            s1 = O.decode16(g["s1"][b], dt)
+        # the residual add is checked from the GPU's own o (and shortcut value)
+        close("x1", g["x1"][b], O.round16(s1 + O.decode16(g["o"][b], dt), dt))
         x1g = O.decode16(g["x1"][b], dt)
         close("h3", g["h3"][b], O.block_input(x1g, L.Q_mlp, L.rms_mlp, L.rms_eps, dt))
         assert np.array_equal(g["idx3"][b], O.topk_indices(g["h3"][b], L.K3)), "idx3"
@@ -79,7 +85,11 @@ def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.
         h4 = O.decode16(g["h4"][b], dt)
         dn, _ = O.stage_down(L, x1g, h4, g["idx4"][b], dt)
         close("down", g["down"][b], dn)
-        x2_want = O.round16(x1g + O.decode16(g["down"][b], dt), dt)
+        s2 = x1g
+        if L.shortcut_mlp is not None:
+            close("s2", g["s2"][b], O.stage_shortcut(x1g, L.shortcut_mlp, dt))
+            s2 = O.decode16(g["s2"][b], dt)
+        x2_want = O.round16(s2 + O.decode16(g["down"][b], dt), dt)
         if L.adapter is not None:
             close("x2", g["x2"][b], x2_want)
             close("x_out", g["x_out"][b], O.stage_adapter(L, O.decode16(g["x2"][b], dt), dt))

@@ -101,6 +101,78 @@ def test_folded_stack_tiny(api, fused_mode):
         cur = out
 
 
+@pytest.mark.parametrize("B", [1, 3])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_shortcut_adapter_stack_tiny(api, fused_mode, B, dtype):
+    """Block-level rotations with every rotation absorbed and a residual adapter on each shortcut; at
+    batch 1 with the fused kernels each adapter shares the launch of the block's first projection."""
+    shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, dtype)
+    layers, bits, Qa, Ws, src = cases.build_shortcut_stack(shape, 3, 0.4, seed=63, n_cal=1024)
+    xb = O.encode16(O.rotate(src.draw(B, seed=9), Qa[0]), dtype)
+    cur = to_dev(xb, dtype)
+    for L, b in zip(layers, bits):
+        case = cases.LayerCase(shape, b, L, {}, src)
+        dl = device_layer(case)
+        ws = api.Workspace(dl.workspace_bytes(B))
+        out = torch.zeros_like(cur)
+        tr = dl.trace_buffers(B)
+        assert "s1" in tr and "s2" in tr
+        api.layer_forward(dl, cur, out, ws, tr)
+        torch.cuda.synchronize()
+        check_layer_trace(L, to_bits(cur), tr, out)
+        # without trace buffers the result is the same bits
+        out2 = torch.zeros_like(cur)
+        api.layer_forward(dl, cur, out2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+        cur = out
+
+
+@pytest.mark.parametrize("side_g,main_g", [(256, 256), (64, 448), (512, 512), (8, 16)])
+def test_shortcut_adapter_launch_shapes(api, side_g, main_g):
+    """Every split of the shared launch between the projection and its adapter gives the same stages."""
+    shape = synth.LayerShape("ragged", 1096, 1096, 1096, 1160, 8, "f16")
+    layers, bits, Qa, Ws, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=65, n_cal=2048)
+    api.set_tuning(5, main_g)
+    api.set_tuning(6, side_g)
+    try:
+        case = cases.LayerCase(shape, bits[0], layers[0], {}, src)
+        xb = O.encode16(O.rotate(src.draw(1, seed=3), Qa[0]), "f16")
+        dl = device_layer(case)
+        ws = api.Workspace(dl.workspace_bytes(1))
+        x = to_dev(xb, "f16")
+        out = torch.zeros_like(x)
+        tr = dl.trace_buffers(1)
+        api.layer_forward(dl, x, out, ws, tr)
+        torch.cuda.synchronize()
+        check_layer_trace(layers[0], xb, tr, out)
+    finally:
+        api.set_tuning(5, 256)
+        api.set_tuning(6, 192)
+
+
+def test_config1_llama2_7b_shortcut_form_full_size(api):
+    """The benchmark layer in the deployed block-level form: rotations absorbed, two 4096 x 4096
+    residual adapters on the shortcuts, 40 % sparsity, batch 1."""
+    print("building llama2-7b shortcut-form case", flush=True)
+    shape = synth.SHAPES["llama2-7b"]
+    layers, bits, Qa, Ws, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=synth.seed_for(1, 0), n_cal=4096)
+    L = layers[0]
+    assert (L.K1, L.K2, L.K3, L.K4) == (2457, 2457, 2457, 6604)
+    case = cases.LayerCase(shape, bits[0], L, {}, src)
+    xb = O.encode16(O.rotate(src.draw(1, synth.seed_for(1, 5)), Qa[0]), "f16")
+    dl = device_layer(case)
+    ws = api.Workspace(dl.workspace_bytes(1))
+    x = to_dev(xb, "f16")
+    out = torch.zeros_like(x)
+    tr = dl.trace_buffers(1)
+    print("running", flush=True)
+    api.layer_forward(dl, x, out, ws, tr)
+    torch.cuda.synchronize()
+    worst = check_layer_trace(L, xb, tr, out)
+    print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
 def test_config1_llama2_7b_layer_full_size(api):
     """The benchmark configuration: LLaMA2-7B-shaped layer, fp16, 40 % sparsity, batch 1, with
     PCA rotations from 4096 synthetic calibration tokens."""
