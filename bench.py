@@ -26,9 +26,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script scaled by a 1 GiB copy (profiles/gemv_rows_llama2_7b_layer_b1_s40_hbm_traffic.txt).
+# script scaled by a 1 GiB copy (profiles/*_hbm_traffic.txt).
 # Keyed by (config, batch, sparsity, form); other workloads have not been counted.
-MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4, "explicit"): 63.2e6}
+MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4, "explicit"): 63.2e6, (1, 1, 0.4, "shortcut"): 79.8e6}
 
 CONFIGS = {
     1: dict(shape="llama2-7b", workload="LLaMA2-7B-shaped decoder layer, fp16, batch 1, 40% sparsity, "
@@ -517,6 +517,19 @@ def main():
                     "p90": round(step_us[(len(step_us) * 9) // 10], 2), "n": len(step_us)}
         if B == 1:
             sparse_launch_us = (stage_us["qkv"] + stage_us["o"] + stage_us["gu"] + stage_us["down"]) / 4.0
+        if B == 1 and shortcut_form:
+            # In this form the step IS four launches of the fused kernel and nothing else, so the launch
+            # time is the step time / 4, taken with HIP events around graph replays on the launch stream
+            # (the per-stage events above each add the cost of an event record to their interval).
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g_layer.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(replays):
+                g_layer.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            sparse_launch_us = e0.elapsed_time(e1) * 1e3 / (replays * nsets * 4)
     # rows a launch has to read: the kept rows at batch 1, the union of the tokens' kept rows otherwise
     U = [int(torch.unique(trace[n]).numel()) for n in ("idx1", "idx2", "idx3", "idx4")]
     sel_bytes_layer = 2 * (U[0] * d_qkv + U[1] * d + U[2] * 2 * d_ff + U[3] * d)
@@ -636,8 +649,10 @@ def main():
                                  if args.alpha == "1.0,1.0" else None),
                      "kernel": (("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step "
                                  + ("(two of them carry a residual adapter in the same launch; its bytes are counted), "
-                                    if shortcut_form else ", ") +
-                                 "timed by HIP events recorded inside larosa_layer_forward") if B == 1 else
+                                    if shortcut_form else ", ")
+                                 + ("timed by HIP events around graph replays of the step (= exactly these 4 launches)"
+                                    if shortcut_form else "timed by HIP events recorded inside larosa_layer_forward"))
+                                if B == 1 else
                                 "skinny_mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
                      "bytes_per_launch": sel_bytes_launch, "us_per_launch": round(sparse_launch_us, 3)},
         "cpu_baseline": cpu,
@@ -652,6 +667,7 @@ def main():
             "layer_GBs_on_all_bytes": round(all_bytes_layer / (graph_us * 1e-6) / 1e9, 1),
             "sparse_projections_us_per_layer": round(sparse_proj_layer_us, 2),
             "stage_us_in_layer": None if stage_us is None else {k: round(v, 2) for k, v in stage_us.items()},
+            "stage_us_note": "eager launches, each interval includes one HIP event record (an empty stage reads ~5 us)",
             "eager_step_us_percentiles": step_pct,      # per-step HIP events (first to last kernel of a step)
             "standalone_sparse_gemv_us_per_launch": round(standalone_launch_us, 3),
             "per_projection": per_proj,
