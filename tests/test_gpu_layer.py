@@ -151,6 +151,45 @@ def test_shortcut_adapter_launch_shapes(api, side_g, main_g):
         api.set_tuning(6, 192)
 
 
+@pytest.mark.parametrize("B,form", [(1, "shortcut"), (1, "explicit"), (4, "explicit"), (3, "shortcut")])
+def test_layer_in_a_hip_graph_replays_to_the_eager_bits(api, B, form):
+    """The bench times graph replays: a captured layer step must give the eager result on every replay,
+    with other work and synchronisations between the replays (arrival counters return to zero by
+    themselves, nothing in the step is a memset)."""
+    shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "f16")
+    if form == "shortcut":
+        layers, bits, Qa, _, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=67, n_cal=1024)
+        case = cases.LayerCase(shape, bits[0], layers[0], {}, src)
+    else:
+        case = cases.build_block_layer(shape, 0.4, seed=67, n_cal=1024, with_adapter=True)
+    xb, _ = cases.tokens(case, B, seed=4)
+    dl = device_layer(case)
+    ws = api.Workspace(dl.workspace_bytes(B))
+    x = to_dev(xb, "f16")
+    eager = torch.zeros_like(x)
+    api.layer_forward(dl, x, eager, ws)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(x)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        api.layer_forward(dl, x, out, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        api.layer_forward(dl, x, out, ws)
+    for rep in range(4):
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        other = torch.zeros_like(x)
+        api.layer_forward(dl, x, other, ws)          # eager work on the same workspace between replays
+        torch.cuda.synchronize()
+        assert torch.equal(other.view(torch.int16), eager.view(torch.int16))
+
+
 def test_config1_llama2_7b_shortcut_form_full_size(api):
     """The benchmark layer in the deployed block-level form: rotations absorbed, two 4096 x 4096
     residual adapters on the shortcuts, 40 % sparsity, batch 1."""
