@@ -37,6 +37,9 @@ CONFIGS = {
     2: dict(shape="llama3-8b", workload="LLaMA3-8B-shaped decoder layer (GQA), bf16", n_cal=4096, latent="gauss"),
     3: dict(shape="llama2-70b", workload="LLaMA2-70B-shaped decoder layer on one GPU, bf16", n_cal=8192,
             latent="t3"),
+    4: dict(shape="llama2-7b", workload="32-layer LLaMA2-7B-shaped projection stack, fp16, per-layer rotations with a "
+                                        "4096 x 4096 residual adapter between layers", n_cal=4096, latent="gauss",
+            n_layers=32),
 }
 
 
@@ -284,6 +287,101 @@ def threshold_report(args, api, torch, shape, cfg, dev):
     print(json.dumps(report), flush=True)
 
 
+def stack_report(args, api, torch, shape, cfg, dev):
+    """The whole projection stack of a 7B-shaped model for one decode step: n_layers layers with
+    their own weights (13 GB in all) and their own rotation Q_l, every rotation absorbed; the
+    residual adapter Q_l^T Q_{l+1} sits on the MLP shortcut (so it shares gate|up's launch at batch 1)
+    and down carries Q_{l+1} on its output side.  Rotations are seeded orthogonal matrices, adapters
+    are built with larosa_residual_adapter, folded weights of Gaussian weights are Gaussian and drawn
+    directly.  One HIP graph holds the n_layers calls; the dense comparator runs the four dense
+    projections of every layer over the same weights."""
+    td = torch.float16 if shape.dtype == "f16" else torch.bfloat16
+    d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff
+    d_qkv = d_q + 2 * d_kv
+    p, B, n_layers = args.sparsity, args.batch, cfg["n_layers"]
+    from paper_2507_01299_amd import allocation, prepare
+    K1, K2, K3, K4 = allocation.kept_counts(d, d_q, d_ff, p, 1.0, 1.0)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1299 * 1000 + 40)
+
+    def gauss(r, c):
+        return (torch.randn(r, c, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(td)
+
+    def basis():
+        q, r = torch.linalg.qr(torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32))
+        return (q * torch.sign(torch.diagonal(r))[None, :]).contiguous()
+
+    scratch = api.OfflineScratch(d, shape.dtype)
+    Q_prev = basis()
+    layers, weights = [], []
+    for l in range(n_layers):
+        Q_next = basis()
+        A = torch.empty(d, d, dtype=td, device=dev)
+        api.residual_adapter(Q_prev, Q_next, A, shape.dtype, scratch)
+        w = dict(Wqkv=gauss(d, d_qkv), Wo=gauss(d_q, d), Wgu=gauss(d, 2 * d_ff), Wdown=gauss(d_ff, d), A=A)
+        weights.append(w)
+        layers.append(api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, w["Wqkv"], w["Wo"], w["Wgu"],
+                                w["Wdown"], shape.dtype, rms_eps=prepare.RMS_EPS, shortcut_mlp=A))
+        Q_prev = Q_next
+    torch.cuda.synchronize()
+    env = torch.arange(1, d + 1, device=dev, dtype=torch.float32) ** -0.8
+    x0 = (torch.randn(B, d, generator=gen, device=dev, dtype=torch.float32) * env * 8.0).to(td).contiguous()
+    bufs = [torch.zeros_like(x0), torch.zeros_like(x0)]
+    ws = api.Workspace(layers[0].workspace_bytes(B))
+
+    def stack():
+        cur = x0
+        for i, L in enumerate(layers):
+            api.layer_forward(L, cur, bufs[i & 1], ws)
+            cur = bufs[i & 1]
+
+    reps = max(2, args.steps // n_layers)
+    stack_us = _graph_event_us(torch, stack, 1, reps)
+    assert bool(torch.isfinite(bufs[(n_layers - 1) & 1].float()).all())
+    ys = dict(qkv=torch.zeros(B, d_qkv, dtype=td, device=dev), o=torch.zeros(B, d, dtype=td, device=dev),
+              gu=torch.zeros(B, 2 * d_ff, dtype=td, device=dev), down=torch.zeros(B, d, dtype=td, device=dev))
+    xin = dict(qkv=x0, o=gauss(B, d_q), gu=x0, down=gauss(B, d_ff))
+
+    def dense_stack():
+        for w in weights:
+            api.dense_gemv(w["Wqkv"], xin["qkv"], ys["qkv"], shape.dtype, ws)
+            api.dense_gemv(w["Wo"], xin["o"], ys["o"], shape.dtype, ws)
+            api.dense_gemv(w["Wgu"], xin["gu"], ys["gu"], shape.dtype, ws)
+            api.dense_gemv(w["Wdown"], xin["down"], ys["down"], shape.dtype, ws)
+
+    dense_us = _graph_event_us(torch, dense_stack, 1, reps)
+    lin_w = [[w["Wqkv"].T.contiguous(), w["Wo"].T.contiguous(), w["Wgu"].T.contiguous(), w["Wdown"].T.contiguous()]
+             for w in weights[:8]]
+    lin_x = [xin["qkv"], xin["o"], xin["gu"], xin["down"]]
+
+    def blas8():
+        for wset in lin_w:
+            for w_, x_ in zip(wset, lin_x):
+                torch.nn.functional.linear(x_, w_)
+
+    blas_us = _graph_event_us(torch, blas8, 1, reps) * (n_layers / 8.0)
+    sel = 2.0 * (K1 * d_qkv + K2 * d + K3 * 2 * d_ff + K4 * d) if B == 1 else None
+    all_bytes = None if sel is None else sel + 2.0 * d * d
+    report = {
+        "metric": "us_per_token_projection_stack", "value": round(stack_us, 2), "unit": "us", "n_gpus": 1,
+        "steps": reps, "warmup": 1, "ms_per_step": round(stack_us / 1e3, 5), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg['workload']}; batch {B}; sparsity {p}", "shape": shape.name, "batch": B,
+                   "layers": n_layers, "K": [K1, K2, K3, K4], "launch": "one HIP graph of the whole stack"},
+        "roofline": None if all_bytes is None else {
+            "bound": "hbm", "achieved": round(all_bytes * n_layers / stack_us / 1e3, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(all_bytes * n_layers / stack_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+            "kernel": "whole stack: kept rows of the four projections + one adapter per layer over the stack time"},
+        "cpu_baseline": None,
+        "extra": {"us_per_layer": round(stack_us / n_layers, 2), "tokens_per_s": round(B * 1e6 / stack_us, 1),
+                  "dense_gemv_stack_us": round(dense_us, 2), "blas_linear_stack_us": round(blas_us, 2),
+                  "speedup_vs_own_dense": round(dense_us / stack_us, 3),
+                  "speedup_vs_blas_dense": round(blas_us / stack_us, 3),
+                  "weights_GB": round(n_layers * 2.0 * (d * d_qkv + d_q * d + d * 2 * d_ff + d_ff * d + d * d) / 1e9, 2)},
+    }
+    print(json.dumps(report), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -338,6 +436,8 @@ def main():
     shape = synth.SHAPES[cfg["shape"]]
     if args.offline:
         return offline_report(args, api, torch, shape, cfg, dev)
+    if args.config == 4:
+        return stack_report(args, api, torch, shape, cfg, dev)
     if args.w4:
         return w4_report(args, api, torch, shape, cfg, dev)
     if args.threshold_comparator:
