@@ -25,12 +25,15 @@ size_t gemv_partial_bytes_bound(int B, int d_in_max, int d_out_max) {
   const long nstrips = (d_out_max + sc - 1) / sc;
   long G = tuning().g_target > 0 ? tuning().g_target : 512;
   if (G < nstrips) G = nstrips;
+  // the 4-bit kernel's wide geometry: per-token launches, 2048-column strips (4x the partial per workgroup)
+  const size_t wide = static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * 2048 * sizeof(float);
   if (B > 1) {   // batched kernels: chunk is capped, so very large products use more workgroups
     const long by_rows = (nstrips * d_in_max + kBatchChunkMax - 1) / kBatchChunkMax;
     if (G < by_rows) G = by_rows;
     B = (B + 31) / 32 * 32;   // token groups are padded
   }
-  return static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * sc * sizeof(float);
+  const size_t narrow = static_cast<size_t>(B) * static_cast<size_t>(G) * 2 * sc * sizeof(float);
+  return narrow > wide ? narrow : wide;
 }
 
 size_t batched_partial_bytes(const GemvPlan& p, int B, bool coef_scale) {
@@ -695,7 +698,7 @@ int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, con
   w.Wq = static_cast<const uint32_t*>(Wq);
   w.scales = static_cast<const uint16_t*>(scales);
   w.ng = (d_out + 127) / 128;
-  const GemvPlan p = plan_gemv(d_out, K);
+  const GemvPlan p = plan_gemv(d_out, K, 0, w4_strip_cols(d_out));
   if (static_cast<size_t>(B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
   const size_t need = kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float);
   if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
@@ -746,6 +749,10 @@ int larosa_set_tuning(int key, int value) {
     case 6:
       if (value < 8 || value > 2048) return LAROSA_EINVAL;
       tuning().side_g = value;
+      return LAROSA_OK;
+    case 7:
+      if (value < 2048 || value > (1 << 30)) return LAROSA_EINVAL;
+      tuning().w4_wide_min_cols = value;
       return LAROSA_OK;
     default:
       return LAROSA_EINVAL;

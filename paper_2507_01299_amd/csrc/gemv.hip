@@ -45,10 +45,10 @@ Tuning& tuning() {
   return t;
 }
 
-GemvPlan plan_gemv(int d_out, int K, int g_hint) {
+GemvPlan plan_gemv(int d_out, int K, int g_hint, int strip_cols) {
   GemvPlan p;
-  p.strip_cols = kStripCols;
-  p.nstrips = (d_out + kStripCols - 1) / kStripCols;
+  p.strip_cols = strip_cols;
+  p.nstrips = (d_out + strip_cols - 1) / strip_cols;
   const long T = static_cast<long>(p.nstrips) * K;
   // 256 compute units: one workgroup each for small problems, two each otherwise
   long G = g_hint > 0 ? g_hint : tuning().g_target > 0 ? tuning().g_target : (T < 32768 ? 256 : 512);
@@ -56,7 +56,7 @@ GemvPlan plan_gemv(int d_out, int K, int g_hint) {
   if (G < p.nstrips) G = p.nstrips;
   p.chunk = static_cast<int>((T + G - 1) / G);
   p.G = static_cast<int>((T + p.chunk - 1) / p.chunk);
-  p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;
+  p.partial_floats = static_cast<size_t>(p.G) * 2 * strip_cols;
   return p;
 }
 

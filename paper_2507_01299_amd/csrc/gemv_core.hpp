@@ -90,9 +90,9 @@ struct Epilogue {
   int d_in, d_out;
 };
 
-template <int RW>
+template <int RW, int NA = 8>
 struct GemvShared {
-  float red[RW > 1 ? RW - 1 : 1][8][64];
+  float red[RW > 1 ? RW - 1 : 1][NA][64];
   float blockred[RW];
   int last;
 };
@@ -100,32 +100,33 @@ struct GemvShared {
 // Sum the RW row-waves through LDS, hand the strip partial to the workspace, and -- in the
 // workgroup that arrives last at the strip -- add all partials in workgroup order, apply the
 // epilogue and store.  Must be called by every lane of the workgroup; ends with a barrier.
+// NA = fp32 accumulators (consecutive output columns) per lane; a strip is 64 * NA columns wide.
 //
 // Partials travel as relaxed agent-scope 64-bit atomics: such accesses are coherent across the
 // chip's L2 slices by themselves, so no cache write-back / invalidate is needed (a release/acquire
 // fence pair per wave costs more than the whole mat-vec here).  Order: every lane waits for its
 // stores to complete, the workgroup barrier joins the lanes, then one lane bumps the strip's
 // arrival counter; the workgroup that observes the last arrival therefore reads completed stores.
-// Slot layout [4][64] of float pairs keeps each store instruction one contiguous 512-byte run.
-template <typename T, int RW>
-__device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment& sg, int seg_no, int b, int g, int G,
+// Slot layout [NA/2][64] of float pairs keeps each store instruction one contiguous 512-byte run.
+template <typename T, int RW, int NA = 8>
+__device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segment& sg, int seg_no, int b, int g, int G,
                                                   int K, int chunk, int nstrips, float* partial, unsigned* counters,
-                                                  const Epilogue& ep, GemvShared<RW>& sh, int lane, int rw) {
+                                                  const Epilogue& ep, GemvShared<RW, NA>& sh, int lane, int rw) {
   constexpr int NT = RW * 64;
+  constexpr int SC = 64 * NA;
   const int s = sg.s;
-  const int col = s * kStripCols + lane * 8;
-  const bool colv = col < ep.d_out;
+  const int col = s * SC + lane * NA;
 
   if (RW > 1) {
     if (rw > 0) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) sh.red[rw - 1][k][lane] = acc[k];
+      for (int k = 0; k < NA; ++k) sh.red[rw - 1][k][lane] = acc[k];
     }
     __syncthreads();
     if (rw == 0) {
       for (int r = 0; r < RW - 1; ++r) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] += sh.red[r][k][lane];
+        for (int k = 0; k < NA; ++k) acc[k] += sh.red[r][k][lane];
       }
     }
   }
@@ -136,12 +137,12 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment
   bool last = (n_s == 1);
   if (n_s > 1) {
     unsigned long long* slot = reinterpret_cast<unsigned long long*>(
-        partial + ((static_cast<size_t>(b) * G + g) * 2 + seg_no) * kStripCols);
+        partial + ((static_cast<size_t>(b) * G + g) * 2 + seg_no) * SC);
     // one counter per 256 bytes: arrivals at different strips must not share a cache line
     unsigned* ctr = counters + (static_cast<size_t>(b) * nstrips + s) * kCounterStride;
     if (rw == 0) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < NA / 2; ++k) {
         const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(acc[2 * k])) |
                                      (static_cast<unsigned long long>(__float_as_uint(acc[2 * k + 1])) << 32);
         __hip_atomic_store(slot + k * 64 + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -158,26 +159,26 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment
     if (last) {
       // row-wave rw adds partials g_first+rw, g_first+rw+RW, ... (kBatch in flight at a time);
       // the RW sub-sums are then added in wave order through LDS: the order never changes.
-      constexpr int kBatch = 8;
+      constexpr int kBatch = NA <= 8 ? 8 : 2;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+      for (int k = 0; k < NA; ++k) acc[k] = 0.f;
       for (int gg = g_first + rw; gg <= g_last; gg += kBatch * RW) {
-        unsigned long long v[kBatch][4];
+        unsigned long long v[kBatch][NA / 2];
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
           const int g2 = min(gg + q * RW, g_last);
           const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
           const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
-              partial + ((static_cast<size_t>(b) * G + g2) * 2 + sgn) * kStripCols);
+              partial + ((static_cast<size_t>(b) * G + g2) * 2 + sgn) * SC);
 #pragma unroll
-          for (int k = 0; k < 4; ++k)
+          for (int k = 0; k < NA / 2; ++k)
             v[q][k] = __hip_atomic_load(p + k * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
           if (gg + q * RW <= g_last) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
+            for (int k = 0; k < NA / 2; ++k) {
               acc[2 * k] += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
               acc[2 * k + 1] += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
             }
@@ -188,13 +189,13 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment
       if (RW > 1) {
         if (rw > 0) {
 #pragma unroll
-          for (int k = 0; k < 8; ++k) sh.red[rw - 1][k][lane] = acc[k];
+          for (int k = 0; k < NA; ++k) sh.red[rw - 1][k][lane] = acc[k];
         }
         __syncthreads();
         if (rw == 0) {
           for (int r = 0; r < RW - 1; ++r) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) acc[k] += sh.red[r][k][lane];
+            for (int k = 0; k < NA; ++k) acc[k] += sh.red[r][k][lane];
           }
         }
       }
@@ -219,19 +220,23 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[8], const Segment
       for (int w2 = 0; w2 < RW; ++w2) tot += sh.blockred[w2];
       scale = 1.0f / sqrtf(tot / static_cast<float>(ep.d_in) + ep.rms_eps);
     }
-    if (rw == 0 && colv) {
-      float v[8];
+    if (rw == 0) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = acc[k] * scale;
-      const size_t off = static_cast<size_t>(b) * ep.d_out + col;
-      if (ep.residual) {
-        if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
-        float r[8];
-        unpack8<T>(*reinterpret_cast<const uint4*>(ep.residual + off), r);
+      for (int c = 0; c < NA / 8; ++c) {
+        if (col + c * 8 >= ep.d_out) continue;            // d_out % 8 == 0: the eight are valid together
+        float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
+        for (int k = 0; k < 8; ++k) v[k] = acc[c * 8 + k] * scale;
+        const size_t off = static_cast<size_t>(b) * ep.d_out + col + c * 8;
+        if (ep.residual) {
+          if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
+          float r[8];
+          unpack8<T>(*reinterpret_cast<const uint4*>(ep.residual + off), r);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
+        }
+        *reinterpret_cast<uint4*>(ep.y + off) = pack8<T>(v);
       }
-      *reinterpret_cast<uint4*>(ep.y + off) = pack8<T>(v);
     }
   }
   __syncthreads();   // LDS is reused by a following segment

@@ -42,12 +42,13 @@ struct Tuning {
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
   int fused_rw = 8;           // row-waves of the fused kernel: 8 (two workgroups per CU) or 16 (one)
   int side_main_g = 256;      // workgroups of a projection that shares its launch with a shortcut adapter
+  int w4_wide_min_cols = 32768;   // 4-bit kernel: narrowest output that uses the 2048-column geometry
   int side_g = 192;           // workgroups of that adapter (all of both jobs resident at once: 448 of 512 slots)
 };
 Tuning& tuning();
 
 // g_hint > 0 asks for that many workgroups instead of the automatic choice
-GemvPlan plan_gemv(int d_out, int K, int g_hint = 0);
+GemvPlan plan_gemv(int d_out, int K, int g_hint = 0, int strip_cols = 512);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
 
 // The same mat-vec over 4-bit weights (w4.hip): g.W is unused; the row loop reads packed codes and
@@ -59,6 +60,10 @@ struct W4Args {
   int ng;                     // ceil(d_out / 128)
 };
 hipError_t launch_gemv_w4(const W4Args& w, bool bf16, hipStream_t s);
+// 4-bit kernel geometry for this output width: 2048-column strips with 16-byte loads (32 codes per
+// lane and row) when rows are 16-byte aligned and wide enough, else the 512-column strips of the
+// 16-bit kernel with dword loads.
+int w4_strip_cols(int d_out);
 // round-to-nearest codes and scales of a 16-bit weight [d_in, d_out]
 hipError_t launch_quantize_w4(const uint16_t* W, int d_in, int d_out, uint32_t* Wq, uint16_t* scales, bool bf16,
                               hipStream_t s);

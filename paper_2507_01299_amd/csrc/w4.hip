@@ -9,9 +9,11 @@
 // (round-to-nearest codes, symmetric).  Groups run along a row, so the scale folds into the
 // row's coefficient: y[o] = sum_t (h_t s_t,g(o)) (q_t,o - 8).
 //
-// Geometry is that of the 16-bit kernel: a wave owns 512 output columns, a lane 8 of them (one
-// dword per kept row, 256-byte bursts), 16 rows in flight; the -8 offset is applied once per lane
-// as -8 * sum of coefficients.  Reductions, cross-workgroup hand-off and epilogue are shared.
+// Two geometries.  Wide (rows of at least 32768 columns, a multiple of 32): a wave owns 2048 output
+// columns, a lane 32 of them (16 bytes per kept row, 1 KiB bursts, one scale), 8 rows in flight, 32
+// accumulators per lane.  Narrow (anything else): the 16-bit kernel's 512-column strips, one dword
+// per lane and row, 16 rows in flight.  The -8 offset is applied once per lane as -8 * sum of
+// coefficients.  Reductions, cross-workgroup hand-off and epilogue are shared with the 16-bit kernel.
 #include "gemv_core.hpp"
 
 namespace larosa {
@@ -58,6 +60,96 @@ __device__ __forceinline__ void stream_rows_w4(const uint32_t* __restrict__ wcol
   }
 #pragma unroll
   for (int k = 0; k < 8; ++k) acc[k] = fmaf(-8.0f, csum, acc[k]);
+}
+
+// Wide geometry: a lane reads 16 bytes (32 codes, one scale group) per kept row, a wave 2048 columns.
+constexpr int kW4WideAcc = 32;
+constexpr int kW4WideCols = 64 * kW4WideAcc;
+constexpr int kW4WideUnroll = 8;
+
+template <typename T, typename Rows>
+__device__ __forceinline__ void stream_rows_w4_wide(const uint32_t* __restrict__ wcol, int row_dwords,
+                                                    const uint16_t* __restrict__ scol, int ng, const Rows& rows,
+                                                    int ra, int re, float (&acc)[kW4WideAcc]) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  float csum = 0.f;
+  for (int t = ra; t < re; t += kW4WideUnroll) {
+    int j[kW4WideUnroll];
+    u32x4 v[kW4WideUnroll];
+    uint16_t s[kW4WideUnroll];
+#pragma unroll
+    for (int u = 0; u < kW4WideUnroll; ++u) j[u] = rows.row(min(t + u, re - 1));
+#pragma unroll
+    for (int u = 0; u < kW4WideUnroll; ++u) {
+      v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wcol + static_cast<size_t>(j[u]) * row_dwords));
+      s[u] = scol[static_cast<size_t>(j[u]) * ng];
+    }
+#pragma unroll
+    for (int u = 0; u < kW4WideUnroll; ++u) {
+      float c = rows.coef(min(t + u, re - 1), j[u]) * T::to_f32(s[u]);
+      c = (t + u < re) ? c : 0.f;
+      csum += c;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const uint32_t lo = v[u][m] & 0x0F0F0F0Fu;
+        const uint32_t hi = (v[u][m] >> 4) & 0x0F0F0F0Fu;
+        float* a8 = acc + m * 8;
+        a8[0] = fmaf(c, static_cast<float>(lo & 0xFFu), a8[0]);
+        a8[1] = fmaf(c, static_cast<float>(hi & 0xFFu), a8[1]);
+        a8[2] = fmaf(c, static_cast<float>((lo >> 8) & 0xFFu), a8[2]);
+        a8[3] = fmaf(c, static_cast<float>((hi >> 8) & 0xFFu), a8[3]);
+        a8[4] = fmaf(c, static_cast<float>((lo >> 16) & 0xFFu), a8[4]);
+        a8[5] = fmaf(c, static_cast<float>((hi >> 16) & 0xFFu), a8[5]);
+        a8[6] = fmaf(c, static_cast<float>(lo >> 24), a8[6]);
+        a8[7] = fmaf(c, static_cast<float>(hi >> 24), a8[7]);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kW4WideAcc; ++k) acc[k] = fmaf(-8.0f, csum, acc[k]);
+}
+
+template <typename T, int RW, bool INDEXED>
+__global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
+  __shared__ GemvShared<RW, kW4WideAcc> sh;
+  const GemvArgs& a = w.g;
+  const int lane = threadIdx.x & 63;
+  const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const int b = blockIdx.y;
+  const int g = blockIdx.x;
+  const int K = a.K;
+
+  GlobalRows<T, INDEXED> rows;
+  rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
+  rows.h = a.h + static_cast<size_t>(b) * a.d_in;
+  rows.coef_scale = a.coef_scale;
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+  const int row_dwords = a.d_out / 8;
+
+  int f0 = g * a.chunk;
+  const int f1 = min(f0 + a.chunk, a.nstrips * K);
+  Segment sg{f0 / K, 0, 0};
+  sg.t0 = f0 - sg.s * K;
+  int seg_no = 0;
+  while (f0 < f1) {
+    sg.t1 = min(K, sg.t0 + (f1 - f0));
+    const int col = sg.s * kW4WideCols + lane * kW4WideAcc;
+    float acc[kW4WideAcc];
+#pragma unroll
+    for (int k = 0; k < kW4WideAcc; ++k) acc[k] = 0.f;
+    const int n = sg.t1 - sg.t0;
+    const int per = (n + RW - 1) / RW;
+    const int ra = sg.t0 + rw * per;
+    const int re = min(sg.t1, ra + per);
+    if (col < a.d_out)   // d_out % 32 == 0 in this geometry: the lane's 32 columns are valid together
+      stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+    reduce_and_finish<T, RW, kW4WideAcc>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep,
+                                         sh, lane, rw);
+    f0 += sg.t1 - sg.t0;
+    sg.s += 1;
+    sg.t0 = 0;
+    seg_no += 1;
+  }
 }
 
 template <typename T, int RW, bool INDEXED>
@@ -139,6 +231,13 @@ template <typename T>
 hipError_t launch_w4_t(const W4Args& w, hipStream_t st) {
   constexpr int RW = 8;
   dim3 grid(w.g.G, w.g.B), block(RW * 64);
+  if (w4_strip_cols(w.g.d_out) == kW4WideCols) {
+    if (w.g.idx)
+      hipLaunchKernelGGL((gemv_rows_w4_wide_kernel<T, RW, true>), grid, block, 0, st, w);
+    else
+      hipLaunchKernelGGL((gemv_rows_w4_wide_kernel<T, RW, false>), grid, block, 0, st, w);
+    return hipGetLastError();
+  }
   if (w.g.idx)
     hipLaunchKernelGGL((gemv_rows_w4_kernel<T, RW, true>), grid, block, 0, st, w);
   else
@@ -147,6 +246,13 @@ hipError_t launch_w4_t(const W4Args& w, hipStream_t st) {
 }
 
 }  // namespace
+
+int w4_strip_cols(int d_out) {
+  // A strip's finisher reads one partial per contributing workgroup, and a wide partial is 8 KiB: with
+  // few strips (narrow outputs) that read-back outweighs the cheaper row loop (measured: 4096 columns
+  // 30 vs 14 us, 22016 columns 27 vs 23 us, 57344 columns 54 vs 73 us).
+  return (d_out % 32 == 0 && d_out >= tuning().w4_wide_min_cols) ? kW4WideCols : kStripCols;
+}
 
 hipError_t launch_quantize_w4(const uint16_t* W, int d_in, int d_out, uint32_t* Wq, uint16_t* scales, bool bf16,
                               hipStream_t s) {

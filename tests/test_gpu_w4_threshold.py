@@ -49,11 +49,20 @@ def test_quantiser_equals_oracle_bit_for_bit(api, dtype, d_in, d_out):
     assert np.array_equal(Wq.cpu().numpy().view(np.uint32), O.pack_w4(codes))
 
 
+@pytest.fixture(params=[32768, 2048], ids=["narrow", "wide"])
+def w4_geometry(api, request):
+    """The 4-bit kernel's two geometries: 512-column strips with dword loads, and 2048-column strips
+    with 16-byte loads (by default only for outputs of 32768 columns or more; forced here)."""
+    api.set_tuning(7, request.param)
+    yield request.param
+    api.set_tuning(7, 32768)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("B,d_in,d_out,K", [(1, 512, 1024, 256), (3, 1096, 1160, 700), (1, 64, 8, 64), (2, 2048, 4096, 1),
-                                            (1, 1000, 6144, 613)])
-def test_w4_projection_matches_oracle(api, ws, dtype, B, d_in, d_out, K):
-    print(f"sparse_gemv_w4 dtype={dtype} B={B} {d_in}x{d_out} K={K}", flush=True)
+                                            (2, 520, 2080, 300), (1, 4096, 2048, 4096), (1, 1000, 6144, 613)])
+def test_w4_projection_matches_oracle(api, ws, w4_geometry, dtype, B, d_in, d_out, K):
+    print(f"sparse_gemv_w4 dtype={dtype} B={B} {d_in}x{d_out} K={K} geometry={w4_geometry}", flush=True)
     rng = np.random.default_rng(300 + d_in + K)
     codes, sbits = O.quantize_rtn_w4(synth.gaussian_weight(d_in, d_out, 31 + d_in), dtype)
     Wq, sc = _dev_w4(codes, sbits, dtype)
@@ -80,7 +89,7 @@ def test_w4_projection_matches_oracle(api, ws, dtype, B, d_in, d_out, K):
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
 
 
-def test_w4_projection_full_size_gate_up(api, ws):
+def test_w4_projection_full_size_gate_up(api, ws, w4_geometry):
     """gate|up of the 7B-shaped layer (4096 x 22016, 40 % sparsity) in the launch shape the bench times."""
     dtype, d_in, d_out, K = "f16", 4096, 22016, 2458
     print("sparse_gemv_w4 full size", flush=True)
