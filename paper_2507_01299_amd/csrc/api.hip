@@ -89,7 +89,7 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
 // (a.side.W != nullptr: y_side = x_side * W_side over all rows) in the same grid.
 int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   const bool side = a.side.W != nullptr;
-  const GemvPlan p = plan_fused(a.g.d_out, a.g.K, side ? tuning().side_main_g : 0);
+  const GemvPlan p = plan_fused(a.g.d_out, a.g.K, side ? tuning().side_main_g : 0, a.pair_cols);
   size_t slots = static_cast<size_t>(a.g.B) * p.nstrips;
   size_t pfloats = static_cast<size_t>(a.g.B) * p.partial_floats;
   unsigned* counters = static_cast<unsigned*>(ws);
@@ -460,8 +460,9 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
                      const uint16_t* residual, uint16_t* y_pre, uint16_t* h_out, int32_t* idx_out,
                      const void* nscale, const void* sideA = nullptr, const uint16_t* side_x = nullptr,
-                     uint16_t* side_y = nullptr) -> int {
+                     uint16_t* side_y = nullptr, int pair_cols = 0, uint16_t* pair_out = nullptr) -> int {
       FusedArgs a{};
+      a.pair_cols = pair_cols; a.pair_out = pair_out;
       if (sideA) {
         a.side.W = static_cast<const uint16_t*>(sideA);
         a.side.h = side_x; a.side.y = side_y;
@@ -480,32 +481,34 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     };
     // the block's first projection; its shortcut adapter (sc: A, dst) shares the launch
     auto first = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* h, void* h_traced, const void* W,
-                     uint16_t* y, int d_out, int K, int32_t* idx_traced, const void* scA, uint16_t* sc_dst) -> int {
+                     uint16_t* y, int d_out, int K, int32_t* idx_traced, const void* scA, uint16_t* sc_dst,
+                     int pair_cols, uint16_t* pair_out) -> int {
       if (Q) {
         if (int rc = block_input(src, Q, scale, h)) return rc;
         mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
         return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr, scA, src,
-                     sc_dst);
+                     sc_dst, pair_cols, pair_out);
       }
       mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
       return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
-                   static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst);
+                   static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst, pair_cols, pair_out);
     };
-    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1, L->shortcut_attn, s1));
+    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1, L->shortcut_attn, s1, 0,
+                     nullptr));
     mark(2);
     LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, s1 ? s1 : x, static_cast<uint16_t*>(T.o),
                      static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
     mark(3);
-    LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2));
+    // gate|up with paired strips: the workgroups that finish it also store h4 = R(SiLU(gate) * up)
+    LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2, d_ff,
+                     h4));
     mark(5);
     if (d_ff <= kFusedMaxWidth) {
-      LAROSA_TRY(fused(kSrcSilu, gu, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
-                       static_cast<uint16_t*>(T.h4), T.idx4, nullptr));
+      LAROSA_TRY(fused(kSrcPlain, h4, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
+                       nullptr, T.idx4, nullptr));
     } else {
       // a wide intermediate vector makes the per-workgroup selection too long: select once instead
-      TopkSource sc{};
-      sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
-      LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, nullptr, bf, st));
+      LAROSA_HIP(launch_topk(h4, B, d_ff, L->K4, idx4, nullptr, nullptr, st));
       LAROSA_TRY(sparse(L->Wdown, h4, idx4, x2, d_ff, d, L->K4, s2 ? s2 : x1, down));
     }
     mark(6);

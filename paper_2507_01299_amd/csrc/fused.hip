@@ -142,7 +142,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   __syncthreads();
 
   // ---- stream the kept rows of the (at most two) segments
-  const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out};
+  const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out, a.pair_cols, a.pair_out};
 #pragma unroll 1
   for (int seg_no = 0; seg_no < 2; ++seg_no) {
     const int n = seg_no == 0 ? nA : nB;
@@ -155,14 +155,15 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
     rows.idx = lst_idx + (seg_no == 0 ? 0 : nA);
     rows.val = lst_val + (seg_no == 0 ? 0 : nA);
     rows.base = sg.t0;
-    const int col = sg.s * kStripCols + lane * 8;
+    bool col_valid;
+    const int col = strip_lane_col(sg.s, lane, a.g.d_out, a.pair_cols, col_valid);
     float acc[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) acc[k] = 0.f;
     const int per = (n + kFusedRW - 1) / kFusedRW;
     const int ra = sg.t0 + rw * per;
     const int re = min(sg.t1, ra + per);
-    if (col < a.g.d_out) stream_rows<T>(a.g.W + col, a.g.d_out, rows, ra, re, acc);
+    if (col_valid) stream_rows<T>(a.g.W + col, a.g.d_out, rows, ra, re, acc);
     reduce_and_finish<T, kFusedRW>(acc, sg, seg_no, b, g, a.g.G, K, a.g.chunk, a.g.nstrips, a.g.partial,
                                    a.g.counters, ep, sh, lane, rw);
   }
@@ -197,8 +198,9 @@ hipError_t launch_rw(const FusedArgs& a, hipStream_t st) {
 
 int fused_row_waves() { return tuning().fused_rw == 16 ? 16 : 8; }
 
-GemvPlan plan_fused(int d_out, int K, int g_hint) {
-  GemvPlan p = plan_gemv(d_out, K, g_hint);
+GemvPlan plan_fused(int d_out, int K, int g_hint, int pair_cols) {
+  // paired strips: ceil(d_ff / 256) strips of 512 columns (256 gate + 256 up); plan_gemv only needs the count
+  GemvPlan p = plan_gemv(pair_cols > 0 ? (pair_cols + 255) / 256 * kStripCols : d_out, K, g_hint);
   if (fused_row_waves() == 16 && tuning().g_target == 0 && g_hint == 0 && p.G > 256) {
     // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
     const long T = static_cast<long>(p.nstrips) * K;

@@ -88,7 +88,25 @@ struct Epilogue {
   const uint16_t* residual;
   uint16_t* y_pre;
   int d_in, d_out;
+  // Paired strips (gate|up): pair_cols = d_ff > 0 makes strip s cover the gate columns
+  // [256 s, 256 s + 256) on lanes 0..31 and the up columns d_ff + [256 s, 256 s + 256) on lanes 32..63,
+  // so the workgroup that finishes a strip holds both halves of 256 channels and also stores
+  // pair_out[b, c] = R(SiLU(R(gate_c)) * R(up_c)).
+  int pair_cols = 0;
+  uint16_t* pair_out = nullptr;
 };
+
+// First output column of a lane in strip s (8 consecutive columns), and whether the lane has any.
+__device__ __forceinline__ int strip_lane_col(int s, int lane, int d_out, int pair_cols, bool& valid) {
+  if (pair_cols > 0) {
+    const int c = s * 256 + (lane & 31) * 8;
+    valid = c < pair_cols;
+    return (lane >> 5) * pair_cols + c;
+  }
+  const int col = s * kStripCols + lane * 8;
+  valid = col < d_out;
+  return col;
+}
 
 template <int RW, int NA = 8>
 struct GemvShared {
@@ -115,7 +133,9 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
   constexpr int NT = RW * 64;
   constexpr int SC = 64 * NA;
   const int s = sg.s;
-  const int col = s * SC + lane * NA;
+  bool lane_valid = true;
+  const int col = (NA == 8 && ep.pair_cols > 0) ? strip_lane_col(s, lane, ep.d_out, ep.pair_cols, lane_valid)
+                                                : s * SC + lane * NA;
 
   if (RW > 1) {
     if (rw > 0) {
@@ -223,19 +243,34 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
     if (rw == 0) {
 #pragma unroll
       for (int c = 0; c < NA / 8; ++c) {
-        if (col + c * 8 >= ep.d_out) continue;            // d_out % 8 == 0: the eight are valid together
+        const bool ok = lane_valid && col + c * 8 < ep.d_out;   // d_out % 8 == 0: the eight are valid together
         float v[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] = acc[c * 8 + k] * scale;
         const size_t off = static_cast<size_t>(b) * ep.d_out + col + c * 8;
-        if (ep.residual) {
-          if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
-          float r[8];
-          unpack8<T>(*reinterpret_cast<const uint4*>(ep.residual + off), r);
+        if (ok) {
+          if (ep.residual) {
+            if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
+            float r[8];
+            unpack8<T>(*reinterpret_cast<const uint4*>(ep.residual + off), r);
 #pragma unroll
-          for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
+            for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
+          }
+          *reinterpret_cast<uint4*>(ep.y + off) = pack8<T>(v);
         }
-        *reinterpret_cast<uint4*>(ep.y + off) = pack8<T>(v);
+        if (NA == 8 && ep.pair_cols > 0 && ep.pair_out) {
+          // lanes 0..31 hold gate, lanes 32..63 the up values of the same channels (all 64 lanes take part
+          // in the exchange; the product is formed from the stored, i.e. rounded, values)
+          float h[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const float mine = round_store<T>(v[k]);
+            const float up = __shfl(mine, (lane & 31) + 32, kWave);
+            h[k] = silu_f32(mine) * up;
+          }
+          if (ok && lane < 32)
+            *reinterpret_cast<uint4*>(ep.pair_out + static_cast<size_t>(b) * ep.pair_cols + (col + c * 8)) = pack8<T>(h);
+        }
       }
     }
   }
@@ -254,7 +289,7 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
   rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
   rows.h = a.h + static_cast<size_t>(b) * a.d_in;
   rows.coef_scale = a.coef_scale;
-  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out, 0, nullptr};
 
   int f0 = g * a.chunk;
   const int f1 = min(f0 + a.chunk, a.nstrips * K);

@@ -87,8 +87,13 @@ struct FusedArgs {
   // Workgroups [0, side_G) of the grid run it; side.idx == nullptr, own counters and partials.
   GemvArgs side;
   int side_G;                 // 0: no side job
+  // gate|up projection with paired strips: pair_cols = d_ff (g.d_out == 2 d_ff), the finishing
+  // workgroups also store pair_out [B, d_ff] = R(SiLU(gate) * up).  The plan must use d_ff / 256 strips.
+  int pair_cols;
+  uint16_t* pair_out;
 };
-GemvPlan plan_fused(int d_out, int K, int g_hint = 0);
+// pair_cols > 0: strips are 256 channels of gate and of up each (see FusedArgs)
+GemvPlan plan_fused(int d_out, int K, int g_hint = 0, int pair_cols = 0);
 int fused_row_waves();
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
   rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
   rows.h = a.h + static_cast<size_t>(b) * a.d_in;
   rows.coef_scale = a.coef_scale;
-  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out, 0, nullptr};
   const int row_dwords = a.d_out / 8;
 
   int f0 = g * a.chunk;
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
   rows.idx = INDEXED ? a.idx + static_cast<size_t>(b) * K : nullptr;
   rows.h = a.h + static_cast<size_t>(b) * a.d_in;
   rows.coef_scale = a.coef_scale;
-  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out};
+  const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out, 0, nullptr};
   const int row_dwords = a.d_out / 8;
 
   int f0 = g * a.chunk;
