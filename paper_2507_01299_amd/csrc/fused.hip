@@ -2,8 +2,8 @@
 // of the paper: selection and mat-vec in one kernel), for gfx950.
 //
 // Every workgroup rebuilds the block's input vector from its producer (a plain vector, the
-// value heads of q|k|v broadcast to their query heads, SiLU(gate)*up, or the RMS-normed residual
-// stream), runs the exact radix select on it (topk_core.hpp) and keeps, in LDS, only the (row,
+// value heads of q|k|v broadcast to their query heads, or the RMS-normed residual stream; the
+// SiLU(gate)*up vector is stored by the gate|up launch itself, see paired strips below), runs the exact radix select on it (topk_core.hpp) and keeps, in LDS, only the (row,
 // coefficient) pairs of the ranks it will stream.  The vector is at most 64 KiB and comes from
 // L2, so the redundant selection costs about a microsecond per workgroup and removes three
 // dependent kernels (copy/activation, Top-K, and the index/value gathers of the mat-vec) per
@@ -58,18 +58,6 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
         const int head = i / a.head_dim;
         const int src = (head / a.group) * a.head_dim + (i - head * a.head_dim);
         v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * (a.d_q + 2 * a.d_kv) + a.d_q + a.d_kv + src);
-      } else if (a.src_mode == kSrcSilu) {
-        const uint16_t* row = a.src + static_cast<size_t>(b) * 2 * d_in;
-        const uint2 gv = *reinterpret_cast<const uint2*>(row + i);
-        const uint2 uv = *reinterpret_cast<const uint2*>(row + d_in + i);
-        float gt[4], up[4];
-        T::unpack2(gv.x, gt[0], gt[1]); T::unpack2(gv.y, gt[2], gt[3]);
-        T::unpack2(uv.x, up[0], up[1]); T::unpack2(uv.y, up[2], up[3]);
-        uint16_t o[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = T::from_f32(silu_f32(gt[k]) * up[k]);
-        v.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
-        v.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
       } else {
         v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * d_in + i);
       }

@@ -76,7 +76,7 @@ struct FusedArgs {
   GemvArgs g;                 // W, y, sizes, work split, workspace, epilogue; g.h and g.idx unused
   int src_mode;               // where the input vector of width g.d_in comes from:
   const uint16_t* src;        //   kSrcPlain: [B, d_in];  kSrcNorm: x [B, d_in] to be RMS-normed;
-                              //   kSrcGqa: q|k|v [B, d_q+2d_kv];  kSrcSilu: gate|up [B, 2 d_in]
+                              //   kSrcGqa: q|k|v [B, d_q+2d_kv]  (kSrcSilu is a Top-K kernel source only)
   int d_q, d_kv, head_dim, group;
   const uint16_t* norm_scale; // kSrcNorm: [d_in] or nullptr
   float norm_eps;

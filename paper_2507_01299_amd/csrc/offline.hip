@@ -19,6 +19,8 @@
 //    so the operand panels they stream are shared through that XCD's L2.
 //  * X^T X is symmetric: tiles that lie entirely below the diagonal are not computed; their elements are
 //    stored by the tile that computes the mirrored position.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "numeric.hpp"
 
@@ -31,12 +33,10 @@ typedef __bf16 bfloat8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTileM = 256;        // C tile of a workgroup: 256 rows (A columns) x 128 columns
-constexpr int kTileN = 128;
+constexpr int kTileM = 256;        // C tile of a workgroup: 256 rows (A columns) x TN columns, TN = 128 or 256
 constexpr int kKTile = 32;         // k rows per LDS stage
 constexpr int kRowDwords = 17;     // 16 k-pairs + 1 pad: odd stride
 constexpr int kTileDwordsA = kTileM * kRowDwords;
-constexpr int kTileDwordsB = kTileN * kRowDwords;
 constexpr int kPatchM = 4, kPatchN = 8;
 
 template <typename T> struct Mfma;
@@ -96,19 +96,34 @@ __device__ __forceinline__ u32x4 read_operand(const uint32_t* tile, int row, int
   return v;
 }
 
-// One k-tile of both operands in a thread's registers.
-struct Staged {
-  uint4 a[4];
-  uint4 b[2];
-};
-
-// Is the 256 x 128 tile that holds element (row, col) left out of a symmetric product?
-__device__ __forceinline__ bool tile_skipped(int row, int col) {
-  return kTileN * (col / kTileN + 1) <= kTileM * (row / kTileM);
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>)
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
 }
 
-template <typename T, bool A_KMAJOR>
-__global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) {
+// One k-tile of both operands in a thread's registers.
+template <int TN>
+struct Staged {
+  uint4 a[4];
+  uint4 b[TN / 64];
+};
+
+// Is the 256 x TN tile that holds element (row, col) left out of a symmetric product?
+template <int TN>
+__device__ __forceinline__ bool tile_skipped(int row, int col) {
+  return TN * (col / TN + 1) <= kTileM * (row / kTileM);
+}
+
+// TN = 128 is the instantiated shape: 4 x 2 instruction tiles per wave, two workgroups per CU.
+template <typename T, bool A_KMAJOR, int TN>
+__global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(ContractionArgs a) {
+  constexpr int NJ = TN / 64;                    // instruction tiles of a wave along n
+  constexpr int kTileN = TN;
+  constexpr int kTileDwordsB = TN * kRowDwords;
   __shared__ uint32_t lds_a[2][kTileDwordsA];
   __shared__ uint32_t lds_b[2][kTileDwordsB];
 
@@ -122,25 +137,25 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
   const int tn = (patch % a.patches_n) * kPatchN + (within & 7);
   if (tm >= a.tiles_m || tn >= a.tiles_n) return;
   const int m0 = tm * kTileM, n0 = tn * kTileN;
-  if (a.symmetric && tile_skipped(m0, n0)) return;
+  if (a.symmetric && tile_skipped<TN>(m0, n0)) return;
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int g = (lane & 7) + 8 * (w & 1);
   const int kp = (lane >> 3) + 8 * (w >> 1);
-  const int wm = w >> 1, wn = w & 1;    // wave tile: rows wm * 128 .. + 127, columns wn * 64 .. + 63
+  const int wm = w >> 1, wn = w & 1;    // wave tile: rows wm * 128 .. + 127, columns wn * TN/2 .. + TN/2 - 1
 
-  float16v acc[4][2];
+  float16v acc[4][NJ];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int ktiles = (a.Kd + kKTile - 1) / kKTile;
   const int iters = ktiles * a.npairs;
 
-  auto fetch = [&](int it, Staged& st) {
+  auto fetch = [&](int it, Staged<TN>& st) {
     const int p = it / ktiles;
     const int k0 = (it - p * ktiles) * kKTile;
     const uint16_t* Ap = a.A + a.pa[p] * a.a_term_stride;
@@ -153,8 +168,9 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
       for (int r = 0; r < 4; ++r) st.a[r] = load_kcontig(Ap, a.Kd, k0, a.Kd, m0, a.M, (t >> 2) + 64 * r, t & 3);
     }
     load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g, kp, st.b[0], st.b[1]);
+    if (TN == 256) load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g + 16, kp, st.b[NJ - 2], st.b[NJ - 1]);
   };
-  auto stash = [&](int buf, const Staged& st) {
+  auto stash = [&](int buf, const Staged<TN>& st) {
     if (A_KMAJOR) {
       store_kmajor(lds_a[buf], st.a[0], st.a[1], g, kp);
       store_kmajor(lds_a[buf], st.a[2], st.a[3], g + 16, kp);
@@ -163,6 +179,7 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
       for (int r = 0; r < 4; ++r) store_kcontig(lds_a[buf], st.a[r], (t >> 2) + 64 * r, t & 3);
     }
     store_kmajor(lds_b[buf], st.b[0], st.b[1], g, kp);
+    if (TN == 256) store_kmajor(lds_b[buf], st.b[NJ - 2], st.b[NJ - 1], g + 16, kp);
   };
   auto compute = [&](int buf) {
     const uint32_t* At = lds_a[buf];
@@ -170,21 +187,21 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const int dw = s * 8 + (lane >> 5) * 4;
-      u32x4 av[4], bv[2];
+      u32x4 av[4], bv[NJ];
 #pragma unroll
       for (int i = 0; i < 4; ++i) av[i] = read_operand(At, wm * 128 + i * 32 + (lane & 31), dw);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bv[j] = read_operand(Bt, wn * 64 + j * 32 + (lane & 31), dw);
+      for (int j = 0; j < NJ; ++j) bv[j] = read_operand(Bt, wn * (TN / 2) + j * 32 + (lane & 31), dw);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(av[i], bv[j], acc[i][j]);
+        for (int j = 0; j < NJ; ++j) acc[i][j] = Mfma<T>::run(av[i], bv[j], acc[i][j]);
     }
   };
 
   // Tile it is computed from LDS buffer it & 1 while the loads of tile it + 2 are in flight and tile
   // it + 1 (loaded one step earlier) moves from registers to the other buffer: one barrier per tile.
-  Staged s0, s1;
+  Staged<TN> s0, s1;
   fetch(0, s0);
   stash(0, s0);
   if (iters > 1) fetch(1, s1);
@@ -202,19 +219,19 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
     }
   }
 
-  // accumulator register r of lane l: row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (n >= a.N) continue;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
+  // accumulator register r of lane l: row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32.
+  // The tile indices are compile-time constants (static_for): a run-time index into the accumulator
+  // array would move all of it to scratch memory.
+  static_for<4 * NJ>([&](auto ij) {
+    constexpr int i = decltype(ij)::value / NJ;
+    constexpr int j = decltype(ij)::value % NJ;
+    const int n = n0 + wn * (TN / 2) + j * 32 + (lane & 31);
+    if (n < a.N) {
+      static_for<4>([&](auto r4c) {
+        constexpr int r4 = decltype(r4c)::value;
         const int mb = m0 + wm * 128 + i * 32 + 8 * r4 + 4 * (lane >> 5);
-        float v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = acc[i][j][r4 * 4 + q] * a.post_scale;
+        float v[4] = {acc[i][j][r4 * 4 + 0] * a.post_scale, acc[i][j][r4 * 4 + 1] * a.post_scale,
+                      acc[i][j][r4 * 4 + 2] * a.post_scale, acc[i][j][r4 * 4 + 3] * a.post_scale};
         if (a.C16) {
 #pragma unroll
           for (int q = 0; q < 4; ++q)
@@ -230,13 +247,14 @@ __global__ __launch_bounds__(256, 2) void contraction_kernel(ContractionArgs a) 
             }
           // element (n, mb .. mb + 3) of a symmetric product, when the tile it falls in is not computed
           // (M % 4 == 0 and mb % 4 == 0: the four are valid together and share a tile)
-          if (a.symmetric && mb < a.M && tile_skipped(n, mb)) {
+          if (a.symmetric && mb < a.M && tile_skipped<TN>(n, mb)) {
             float4 o4 = make_float4(v[0], v[1], v[2], v[3]);
             *reinterpret_cast<float4*>(a.C32 + static_cast<long>(n) * a.N + mb) = o4;
           }
         }
-      }
+      });
     }
+  });
 }
 
 // fp32 -> NT 16-bit terms with x * pre_scale = t0 + t1 (+ t2) up to the last term's rounding.
@@ -267,27 +285,28 @@ hipError_t launch_split_terms(const float* src, uint16_t* dst, long n, float pre
   return hipGetLastError();
 }
 
-hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s) {
+namespace {
+
+template <typename T, bool A_KMAJOR, int TN>
+hipError_t launch_tiles(ContractionArgs a, hipStream_t s) {
   a.tiles_m = (a.M + kTileM - 1) / kTileM;
-  a.tiles_n = (a.N + kTileN - 1) / kTileN;
+  a.tiles_n = (a.N + TN - 1) / TN;
   a.patches_m = (a.tiles_m + kPatchM - 1) / kPatchM;
   a.patches_n = (a.tiles_n + kPatchN - 1) / kPatchN;
   const long patches = static_cast<long>(a.patches_m) * a.patches_n;
   const long grid = (patches + 7) / 8 * 8 * 32;
   if (grid > 0x7FFFFFFFL) return hipErrorInvalidValue;
-  dim3 gd(static_cast<unsigned>(grid)), bd(256);
-  if (bf16) {
-    if (a_kmajor)
-      hipLaunchKernelGGL((contraction_kernel<BF16, true>), gd, bd, 0, s, a);
-    else
-      hipLaunchKernelGGL((contraction_kernel<BF16, false>), gd, bd, 0, s, a);
-  } else {
-    if (a_kmajor)
-      hipLaunchKernelGGL((contraction_kernel<F16, true>), gd, bd, 0, s, a);
-    else
-      hipLaunchKernelGGL((contraction_kernel<F16, false>), gd, bd, 0, s, a);
-  }
+  hipLaunchKernelGGL((contraction_kernel<T, A_KMAJOR, TN>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, s, a);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s) {
+  // (a 256 x 256 tile with 4 x 4 instruction tiles per wave needs more than the 512 registers of a
+  // lane once two k-tiles of loads are in flight: measured 7x slower through scratch memory)
+  if (bf16) return a_kmajor ? launch_tiles<BF16, true, 128>(a, s) : launch_tiles<BF16, false, 128>(a, s);
+  return a_kmajor ? launch_tiles<F16, true, 128>(a, s) : launch_tiles<F16, false, 128>(a, s);
 }
 
 }  // namespace larosa
