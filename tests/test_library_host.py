@@ -65,12 +65,17 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.larosa_rotate(fake, null, fake, 1, 64, 0, fake, 1 << 20, null) == api.EINVAL
     assert lib.larosa_workspace_init(null, 1 << 20, null) == api.EWORKSPACE
     assert lib.larosa_set_tuning(99, 1) == api.EINVAL
+    # every documented key accepts its default and rejects a value out of range
+    for key, good, bad in ((0, 0, -1), (1, 8, 0), (2, 0, 3), (3, 1, 2), (4, 8, 12), (5, 256, 4), (6, 192, 4),
+                           (7, 32768, 100)):
+        assert lib.larosa_set_tuning(key, bad) == api.EINVAL
+        assert lib.larosa_set_tuning(key, good) == api.OK
 
 
 def test_layer_struct_validation(lib):
     from paper_2507_01299_amd import api
     L = api._Layer(256, 256, 128, 704, 32, 100, 100, 100, 300, 0x1000, 0x1000, 0x1000, 0x1000,
-                   None, None, None, None, None, -1.0, 0, 0)
+                   None, None, None, None, None, -1.0, 0, 0, None, None)
     n = lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2)
     assert n > 0
     L.K4 = 705
@@ -79,6 +84,11 @@ def test_layer_struct_validation(lib):
     L.head_dim = 48
     assert lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2) == 0
     L.head_dim = 32
+    L.shortcut_mlp = 0x1004                      # misaligned adapter
+    assert lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2) == 0
+    L.shortcut_mlp = 0x3000
+    assert lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2) >= n       # two more stage buffers
+    L.shortcut_mlp = None
     fake = ctypes.c_void_p(0x1000)
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, fake, 1, None, fake, n, None) == api.EINVAL  # x_out aliases x
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, ctypes.c_void_p(0x2000), 1, None, fake, 16, None) == api.EWORKSPACE
