@@ -427,10 +427,23 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       a.residual = residual; a.y_pre = y_pre;
       return run_batched(a, bf, ws, gws, st);
     };
+    // block input and its select: with an explicit rotation the matrix pass comes first; with the
+    // rotation absorbed the pre-norm is formed inside the select kernel
+    auto input_and_select = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* h, int K,
+                                int32_t* idx, int stage) -> int {
+      if (Q || !norm) {
+        if (int rc = block_input(src, Q, scale, h)) return rc;
+        mark(stage);
+        return launch_topk(h, B, d, K, idx, nullptr, masked, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+      }
+      mark(stage);
+      TopkSource sc{};
+      sc.mode = kSrcNorm; sc.src = src; sc.h_out = h;
+      sc.norm_scale = static_cast<const uint16_t*>(scale); sc.norm_eps = L->rms_eps;
+      return launch_topk_from(sc, B, d, K, idx, masked, bf, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+    };
     if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
-    LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
-    mark(1);
-    LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, masked, st));
+    LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, idx1, 1));
     LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr));
     mark(2);
     {
@@ -443,9 +456,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     LAROSA_TRY(project(L->Wo, d_q, d, x1, s1 ? s1 : x, o));
     mark(3);
     if (s2) LAROSA_TRY(shortcut(x1, L->shortcut_mlp, s2));
-    LAROSA_TRY(block_input(x1, L->Q_mlp, L->rms_mlp, h3));
-    mark(4);
-    LAROSA_HIP(launch_topk(h3, B, d, L->K3, idx3, nullptr, masked, st));
+    LAROSA_TRY(input_and_select(x1, L->Q_mlp, L->rms_mlp, h3, L->K3, idx3, 4));
     LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr));
     mark(5);
     {

@@ -126,11 +126,13 @@ hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C,
 hipError_t launch_topk(const uint16_t* h, int B, int d, int K, int32_t* idx, uint16_t* vals, uint16_t* masked,
                        hipStream_t s);
 // The same select on a vector that is built on the fly (kSrcGqa from q|k|v, kSrcSilu from gate|up,
-// kSrcPlain from src itself); h_out (nullable) receives the vector [B, d].
+// kSrcNorm = RMS-normed src, kSrcPlain from src itself); h_out (nullable) receives the vector [B, d].
 struct TopkSource {
   int mode;
   const uint16_t* src;
   int d_q, d_kv, head_dim, group;   // kSrcGqa
+  const uint16_t* norm_scale;       // kSrcNorm: [d] or nullptr
+  float norm_eps;
   uint16_t* h_out;
 };
 hipError_t launch_topk_from(const TopkSource& sc, int B, int d, int K, int32_t* idx, uint16_t* masked, bool bf16,

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
       } else {
         v = *reinterpret_cast<const uint2*>(hb + i);
       }
-      if (sc.h_out) *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
+      if (sc.h_out && sc.mode != kSrcNorm) *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
     }
     raw[q * 4 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu);
     raw[q * 4 + 1] = static_cast<uint16_t>(v.x >> 16);
@@ -59,6 +59,43 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
     raw[q * 4 + 3] = static_cast<uint16_t>(v.y >> 16);
   }
   const int nvalid = max(0, min(E, d - base));
+  if (sc.mode == kSrcNorm) {
+    // h = R(x * rsqrt(mean(x^2) + eps) * scale): the pre-norm of a block whose rotation is absorbed
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < E; ++q) {
+      const float xv = (q < nvalid) ? T::to_f32(raw[q]) : 0.f;
+      ss = fmaf(xv, xv, ss);
+    }
+    ss = wave_sum(ss);
+    float* tot_w = reinterpret_cast<float*>(sm.wave_tot);
+    if ((threadIdx.x & 63) == 0) tot_w[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w2 = 0; w2 < kTopkWaves; ++w2) tot += tot_w[w2];
+    __syncthreads();                      // wave_tot is reused by the select
+    const float rinv = 1.0f / sqrtf(tot / static_cast<float>(d) + sc.norm_eps);
+#pragma unroll
+    for (int q = 0; q < E; ++q) {
+      if (q < nvalid) {
+        float xv = T::to_f32(raw[q]) * rinv;
+        if (sc.norm_scale) xv *= T::to_f32(sc.norm_scale[base + q]);
+        raw[q] = T::from_f32(xv);
+      }
+    }
+    if (sc.h_out) {
+#pragma unroll
+      for (int q = 0; q < E / 4; ++q) {
+        const int i = base + q * 4;
+        if (i < d) {
+          uint2 v;
+          v.x = raw[q * 4 + 0] | (static_cast<uint32_t>(raw[q * 4 + 1]) << 16);
+          v.y = raw[q * 4 + 2] | (static_cast<uint32_t>(raw[q * 4 + 3]) << 16);
+          *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
+        }
+      }
+    }
+  }
   const TopkLane st = block_select<kTopkWaves, E>(raw, nvalid, K, sm);
 
   int32_t* idxb = idx + static_cast<size_t>(b) * K;
