@@ -59,6 +59,27 @@ def test_tiny_layer_every_stage(api, fused_mode, dtype, adapter):
     assert np.array_equal(to_bits(out), to_bits(out2))
 
 
+@pytest.mark.parametrize("B", [17, 40, 70])
+def test_large_batches_span_several_token_groups(api, B):
+    """The batched kernels handle 16 or 32 tokens per group: batches that fill one group partly,
+    two groups, and three groups with a ragged last one; both layer forms."""
+    shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "bf16")
+    case = cases.build_block_layer(shape, 0.4, seed=91, n_cal=1024, with_adapter=True)
+    xb, out, tr, dl, ws = _run_layer(api, case, B, seed=12)
+    check_layer_trace(case.layer, xb, tr, out)
+    layers, bits, Qa, _, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=93, n_cal=1024)
+    sc = cases.LayerCase(shape, bits[0], layers[0], {}, src)
+    xb = O.encode16(O.rotate(src.draw(B, seed=13), Qa[0]), "bf16")
+    dl = device_layer(sc)
+    ws = api.Workspace(dl.workspace_bytes(B))
+    x = to_dev(xb, "bf16")
+    out = torch.zeros_like(x)
+    tr = dl.trace_buffers(B)
+    api.layer_forward(dl, x, out, ws, tr)
+    torch.cuda.synchronize()
+    check_layer_trace(layers[0], xb, tr, out)
+
+
 def test_ragged_layer_shapes(api, fused_mode):
     """Widths that are not multiples of the 512-column strip or of the per-lane element run, GQA
     with 4 query heads per value head, K values at both extremes."""
