@@ -31,6 +31,7 @@ struct TopkLane {
   unsigned gt_before;  // kept-by-magnitude elements before this lane's first element
   unsigned eq_before;  // threshold ties before this lane's first element
   unsigned n_gt, n_eq; // this lane's own counts of keys > T and == T
+  unsigned long long m_gt, m_eq;   // bit q set: this lane's element q has key > T / == T
   // ranks [first, end) of the ascending kept list held by this lane
   __device__ __forceinline__ unsigned first_rank() const { return gt_before + min(eq_before, r); }
   __device__ __forceinline__ unsigned end_rank() const { return gt_before + n_gt + min(eq_before + n_eq, r); }
@@ -118,15 +119,19 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(sm.bin2);
   out.r = static_cast<unsigned>(K) - (above1 + sm.above2);
 
-  unsigned n_gt = 0, n_eq = 0;
+  // per-lane bit masks of the two classes (independent compares: no chain from element to element)
+  unsigned long long m_gt = 0, m_eq = 0;
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
     if (q < nvalid) {
-      n_gt += (key > out.T) ? 1u : 0u;
-      n_eq += (key == out.T) ? 1u : 0u;
+      m_gt |= static_cast<unsigned long long>(key > out.T ? 1u : 0u) << q;
+      m_eq |= static_cast<unsigned long long>(key == out.T ? 1u : 0u) << q;
     }
   }
+  const unsigned n_gt = static_cast<unsigned>(__popcll(m_gt)), n_eq = static_cast<unsigned>(__popcll(m_eq));
+  out.m_gt = m_gt;
+  out.m_eq = m_eq;
   const unsigned packed = n_gt | (n_eq << 16);          // each total <= 32768: no carry between halves
   const unsigned incl = wave_scan_inclusive(packed, lane);
   if (lane == 63) sm.wave_tot[wave] = incl;
@@ -140,20 +145,30 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   return out;
 }
 
-// Visit this lane's elements in index order; emit(q, pos) is called for every kept element with
-// its rank pos in the ascending kept list.
+// Visit this lane's kept elements in index order; emit(q, pos) is called for every kept element with
+// its rank pos in the ascending kept list.  Kept = key > T, plus the first r threshold ties in index
+// order; a kept element's rank is the lane's first rank plus the number of kept elements before it
+// in the lane, so every element is handled independently of the others.
 template <int E, typename F>
-__device__ __forceinline__ void for_each_kept(const uint16_t (&raw)[E], int nvalid, TopkLane st, F emit) {
+__device__ __forceinline__ void for_each_kept(const uint16_t (&raw)[E], int nvalid, const TopkLane& st, F emit) {
+  (void)raw; (void)nvalid;
+  // threshold ties of this lane that are kept: its first (r - eq_before) ones
+  unsigned long long eq_keep = st.m_eq;
+  const int want = static_cast<int>(st.r) - static_cast<int>(st.eq_before);
+  if (want < static_cast<int>(st.n_eq)) {            // rare: the tie quota ends inside this lane
+    unsigned long long m = st.m_eq;
+    eq_keep = 0;
+    for (int i = 0; i < want; ++i) {
+      const unsigned long long low = m & (0ull - m);
+      eq_keep |= low;
+      m ^= low;
+    }
+  }
+  const unsigned long long kept = st.m_gt | eq_keep;
+  const unsigned first = st.first_rank();
 #pragma unroll
   for (int q = 0; q < E; ++q) {
-    if (q < nvalid) {
-      const unsigned key = raw[q] & 0x7FFFu;
-      const bool gt = key > st.T;
-      const bool eq = key == st.T;
-      if (gt || (eq && st.eq_before < st.r)) emit(q, st.gt_before + min(st.eq_before, st.r));
-      st.gt_before += gt ? 1u : 0u;
-      st.eq_before += eq ? 1u : 0u;
-    }
+    if ((kept >> q) & 1ull) emit(q, first + static_cast<unsigned>(__popcll(kept & ((1ull << q) - 1ull))));
   }
 }
 
