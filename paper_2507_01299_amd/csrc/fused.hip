@@ -114,14 +114,16 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   // only lanes whose ranks meet this workgroup's two rank ranges (a few percent) walk their elements
   const int p0 = static_cast<int>(st.first_rank()), p1 = static_cast<int>(st.end_rank());
   if (idx_out || (p0 < tA0 + nA && p1 > tA0) || p0 < nB) {
-    for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned upos) {
+    for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned upos, bool kept) {
       const int pos = static_cast<int>(upos);
-      if (pos >= K) return;                 // never taken; keeps a stray rank out of the lists
-      if (idx_out) idx_out[pos] = base + q;
-      int e = -1;
-      if (pos >= tA0 && pos < tA0 + nA) e = pos - tA0;
-      else if (pos < nB) e = nA + pos;
-      if (e >= 0) {
+      if (idx_out && kept) idx_out[pos] = base + q;          // idx_out is uniform over the workgroup
+      // entry of the rank in this workgroup's list: segment A holds ranks [tA0, tA0 + nA), segment B
+      // ranks [0, nB); e < nA + nB <= the list capacity by construction
+      const int eA = pos - tA0;
+      const bool inA = static_cast<unsigned>(eA) < static_cast<unsigned>(nA);
+      const bool inB = pos < nB;
+      const int e = inA ? eA : nA + pos;
+      if (kept && (inA || inB)) {
         lst_idx[e] = base + q;
         lst_val[e] = T::to_f32(raw[q]);
       }

@@ -103,12 +103,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   uint16_t mk[E];
 #pragma unroll
   for (int q = 0; q < E; ++q) mk[q] = 0;
-  for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned pos) {
-    if (pos < static_cast<unsigned>(K)) {   // always true; keeps a stray position inside the row
+  for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned pos, bool kept) {
+    if (kept) {
       idxb[pos] = base + q;
       if (valb) valb[pos] = raw[q];
-      mk[q] = raw[q];
     }
+    mk[q] = kept ? raw[q] : static_cast<uint16_t>(0);
   });
   if (masked) {
     uint16_t* mb = masked + static_cast<size_t>(b) * d;

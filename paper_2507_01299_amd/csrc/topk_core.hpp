@@ -145,8 +145,9 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   return out;
 }
 
-// Visit this lane's kept elements in index order; emit(q, pos) is called for every kept element with
-// its rank pos in the ascending kept list.  Kept = key > T, plus the first r threshold ties in index
+// Visit this lane's elements in index order; emit(q, pos, kept) is called for EVERY element q < E, with
+// kept telling whether it is selected and, if so, pos its rank in the ascending kept list (callers
+// fold `kept` into their store predicate: a branch per element costs more than the stores).  Kept = key > T, plus the first r threshold ties in index
 // order; a kept element's rank is the lane's first rank plus the number of kept elements before it
 // in the lane, so every element is handled independently of the others.
 template <int E, typename F>
@@ -167,9 +168,8 @@ __device__ __forceinline__ void for_each_kept(const uint16_t (&raw)[E], int nval
   const unsigned long long kept = st.m_gt | eq_keep;
   const unsigned first = st.first_rank();
 #pragma unroll
-  for (int q = 0; q < E; ++q) {
-    if ((kept >> q) & 1ull) emit(q, first + static_cast<unsigned>(__popcll(kept & ((1ull << q) - 1ull))));
-  }
+  for (int q = 0; q < E; ++q)
+    emit(q, first + static_cast<unsigned>(__popcll(kept & ((1ull << q) - 1ull))), ((kept >> q) & 1ull) != 0ull);
 }
 
 }  // namespace larosa
