@@ -137,7 +137,11 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   if (lane == 63) sm.wave_tot[wave] = incl;
   __syncthreads();
   unsigned prefix = incl - packed;
-  for (int w = 0; w < wave; ++w) prefix += sm.wave_tot[w];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {          // all totals are read at once; a loop to `wave` would chain the reads
+    const unsigned t = sm.wave_tot[w];
+    prefix += (w < wave) ? t : 0u;
+  }
   out.gt_before = prefix & 0xFFFFu;
   out.eq_before = prefix >> 16;
   out.n_gt = n_gt;
