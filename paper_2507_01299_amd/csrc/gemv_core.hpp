@@ -151,6 +151,18 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
     }
   }
 
+  // The residual a finishing workgroup adds is fetched now, by every workgroup, so that its latency
+  // overlaps the hand-off below instead of following it (16 bytes per lane of one wave).
+  uint4 res_pref[NA / 8];
+  if (ep.residual && rw == 0) {
+#pragma unroll
+    for (int c = 0; c < NA / 8; ++c) {
+      res_pref[c] = make_uint4(0u, 0u, 0u, 0u);
+      if (lane_valid && col + c * 8 < ep.d_out)
+        res_pref[c] = *reinterpret_cast<const uint4*>(ep.residual + static_cast<size_t>(b) * ep.d_out + col + c * 8);
+    }
+  }
+
   const int g_first = (s * K) / chunk;
   const int g_last = ((s + 1) * K - 1) / chunk;
   const int n_s = g_last - g_first + 1;
@@ -252,7 +264,7 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
           if (ep.residual) {
             if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
             float r[8];
-            unpack8<T>(*reinterpret_cast<const uint4*>(ep.residual + off), r);
+            unpack8<T>(res_pref[c], r);
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
           }
