@@ -80,6 +80,45 @@ def test_large_batches_span_several_token_groups(api, B):
     check_layer_trace(layers[0], xb, tr, out)
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_seeded_random_shapes_and_kept_counts(api, seed):
+    """Seeded random layer shapes (every width a multiple of 8, GQA groups of 1-4), random kept counts
+    including the extremes, batch 1-5, both dtypes, explicit and shortcut forms."""
+    rng = np.random.default_rng(7000 + seed)
+    head_dim = int(rng.choice([8, 16, 24, 32]))
+    kv_heads = int(rng.integers(1, 5))
+    group = int(rng.integers(1, 5))
+    d_kv, d_q = head_dim * kv_heads, head_dim * kv_heads * group
+    d = 8 * int(rng.integers(4, 90))
+    d_ff = 8 * int(rng.integers(4, 200))
+    dtype = "f16" if seed % 2 == 0 else "bf16"
+    shape = synth.LayerShape(f"rand{seed}", d, d_q, d_kv, d_ff, head_dim, dtype)
+
+    def pick(n):
+        return int(rng.choice([1, n, max(1, n // 2), int(rng.integers(1, n + 1))]))
+
+    Ks = (pick(d), pick(d_q), pick(d), pick(d_ff))
+    B = int(rng.integers(1, 6))
+    print(f"shape d={d} d_q={d_q} d_kv={d_kv} d_ff={d_ff} head_dim={head_dim} {dtype} Ks={Ks} B={B}", flush=True)
+    case = cases.build_block_layer(shape, 0.4, seed=100 + seed, n_cal=max(256, 2 * d), Ks=Ks,
+                                   with_adapter=bool(seed % 3 == 0))
+    xb, out, tr, dl, ws = _run_layer(api, case, B, seed=seed)
+    check_layer_trace(case.layer, xb, tr, out)
+    layers, bits, Qa, _, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=200 + seed, n_cal=max(256, 2 * d))
+    L = layers[0]
+    L.K1, L.K2, L.K3, L.K4 = Ks
+    sc = cases.LayerCase(shape, bits[0], L, {}, src)
+    xb = O.encode16(O.rotate(src.draw(B, seed=seed), Qa[0]), dtype)
+    dl = device_layer(sc)
+    ws = api.Workspace(dl.workspace_bytes(B))
+    x = to_dev(xb, dtype)
+    out = torch.zeros_like(x)
+    tr = dl.trace_buffers(B)
+    api.layer_forward(dl, x, out, ws, tr)
+    torch.cuda.synchronize()
+    check_layer_trace(L, xb, tr, out)
+
+
 def test_ragged_layer_shapes(api, fused_mode):
     """Widths that are not multiples of the 512-column strip or of the per-lane element run, GQA
     with 4 query heads per value head, K values at both extremes."""
