@@ -12,13 +12,16 @@
 //      elements before its own, so an index-ordered compaction keeps every key > T and the first
 //      r keys == T: ascending indices and the lower-index tie rule with no sort.
 #pragma once
+#include <cstddef>
+
 #include "numeric.hpp"
 
 namespace larosa {
 
 template <int NW>
 struct TopkShared {
-  unsigned hist_w[NW][256];
+  unsigned hist_w[NW][256];   // pass 1, one copy per wave
+  unsigned hist2_w[NW][128];  // pass 2 (its own region, so both are cleared in one step)
   unsigned wave_tot[NW];
   int bin, bin2;            // pass-1 / pass-2 bin holding the K-th largest key
   unsigned above, above2;   // counts strictly above those bins
@@ -45,10 +48,11 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  unsigned* flat = &sm.hist_w[0][0];   // NW x 256 words: pass 1 uses all, pass 2 the first NW x 128
+  unsigned* flat = &sm.hist_w[0][0];   // hist_w and hist2_w are adjacent: NW x 384 words
 
   // ---- pass 1: top 8 key bits
-  for (int i = tid; i < NW * 256; i += NT) flat[i] = 0u;
+  static_assert(offsetof(TopkShared<NW>, hist2_w) == sizeof(unsigned) * NW * 256, "histograms must be adjacent");
+  for (int i = tid; i < NW * 384; i += NT) flat[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < E; ++q)
@@ -82,13 +86,11 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const int bin1 = sm.bin;
   const unsigned above1 = sm.above;
 
-  // ---- pass 2: low 7 bits inside bin1 (the pass-1 reads of hist_w are complete: wave 0 passed the barrier)
-  for (int i = tid; i < NW * 128; i += NT) flat[i] = 0u;
-  __syncthreads();
+  // ---- pass 2: low 7 bits inside bin1
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&flat[wave * 128 + (key & 127u)], 1u);
+    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&sm.hist2_w[wave][key & 127u], 1u);
   }
   __syncthreads();
   if (wave == 0) {
@@ -98,7 +100,7 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
       const int bin = 127 - (lane * 2 + q);
       unsigned t = 0;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) t += flat[w * 128 + bin];
+      for (int w = 0; w < NW; ++w) t += sm.hist2_w[w][bin];
       c[q] = t;
       local += t;
     }
