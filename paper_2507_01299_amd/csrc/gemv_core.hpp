@@ -289,10 +289,16 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
   __syncthreads();   // LDS is reused by a following segment
 }
 
+constexpr int kRowListMax = 2048;   // (strip, rank) pairs of a workgroup whose rows are staged in LDS
+
 // The row-streaming mat-vec of workgroup g for token b: its share of the (strip, kept row) pairs,
-// at most two segments, each reduced and handed over by reduce_and_finish.
+// at most two segments, each reduced and handed over by reduce_and_finish.  With an index list the
+// workgroup first copies its ranks' (row, coefficient) pairs into LDS (coalesced), so the row loop
+// has no dependent index -> activation -> address chain through global memory.
 template <typename T, int RW, bool INDEXED>
 __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, GemvShared<RW>& sh) {
+  __shared__ int lst_idx[INDEXED ? kRowListMax : 1];
+  __shared__ float lst_val[INDEXED ? kRowListMax : 1];
   const int lane = threadIdx.x & 63;
   const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
   const int K = a.K;
@@ -307,7 +313,19 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
   const int f1 = min(f0 + a.chunk, a.nstrips * K);
   Segment sg{f0 / K, 0, 0};
   sg.t0 = f0 - sg.s * K;
+  const bool staged = INDEXED && (f1 - f0) <= kRowListMax;   // uniform over the workgroup
+  if (staged) {
+    const int nA = min(K - sg.t0, f1 - f0);     // entries [0, nA): ranks t0 + e; entries [nA, ..): ranks e - nA
+    for (int e = threadIdx.x; e < f1 - f0; e += RW * 64) {
+      const int t = e < nA ? sg.t0 + e : e - nA;
+      const int j = rows.row(t);
+      lst_idx[e] = j;
+      lst_val[e] = rows.coef(t, j);
+    }
+    __syncthreads();
+  }
   int seg_no = 0;
+  int list_base = 0;
   while (f0 < f1) {
     sg.t1 = min(K, sg.t0 + (f1 - f0));
     const int col = sg.s * kStripCols + lane * 8;
@@ -319,9 +337,20 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
     const int per = (n + RW - 1) / RW;
     const int ra = sg.t0 + rw * per;
     const int re = min(sg.t1, ra + per);
-    if (col < a.d_out) stream_rows<T>(a.W + col, a.d_out, rows, ra, re, acc);
+    if (col < a.d_out) {
+      if (staged) {
+        LdsRows lr;
+        lr.idx = lst_idx + list_base;
+        lr.val = lst_val + list_base;
+        lr.base = sg.t0;
+        stream_rows<T>(a.W + col, a.d_out, lr, ra, re, acc);
+      } else {
+        stream_rows<T>(a.W + col, a.d_out, rows, ra, re, acc);
+      }
+    }
     reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
                              rw);
+    list_base += n;
     f0 += sg.t1 - sg.t0;
     sg.s += 1;
     sg.t0 = 0;
