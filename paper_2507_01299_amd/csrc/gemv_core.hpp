@@ -153,8 +153,10 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
 
   // The residual a finishing workgroup adds is fetched now, by every workgroup, so that its latency
   // overlaps the hand-off below instead of following it (16 bytes per lane of one wave).
-  uint4 res_pref[NA / 8];
-  if (ep.residual && rw == 0) {
+  // (only in the 8-accumulator geometry: the wide one has no registers to spare for it)
+  constexpr bool kPrefetchResidual = NA == 8;
+  uint4 res_pref[kPrefetchResidual ? NA / 8 : 1];
+  if (kPrefetchResidual && ep.residual && rw == 0) {
 #pragma unroll
     for (int c = 0; c < NA / 8; ++c) {
       res_pref[c] = make_uint4(0u, 0u, 0u, 0u);
@@ -264,7 +266,8 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
           if (ep.residual) {
             if (ep.y_pre) *reinterpret_cast<uint4*>(ep.y_pre + off) = pack8<T>(v);
             float r[8];
-            unpack8<T>(res_pref[c], r);
+            unpack8<T>(kPrefetchResidual ? res_pref[kPrefetchResidual ? c : 0]
+                                         : *reinterpret_cast<const uint4*>(ep.residual + off), r);
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = r[k] + round_store<T>(v[k]);
           }
@@ -291,6 +294,25 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], const Segmen
 
 constexpr int kRowListMax = 2048;   // (strip, rank) pairs of a workgroup whose rows are staged in LDS
 
+// Copy the (row, coefficient) pairs of a workgroup's `count` consecutive (strip, rank) pairs, starting
+// at rank t0 of its first strip, into LDS: entries [0, nA) are ranks t0 + e of the first strip,
+// entries [nA, count) ranks e - nA of the next one (nA = min(K - t0, count)).  Returns false (and
+// copies nothing) when the list does not fit; ends with a barrier otherwise.  Uniform over the workgroup.
+template <int NT, int CAP = kRowListMax, typename Rows>
+__device__ __forceinline__ bool stage_row_list(const Rows& rows, int t0, int count, int K, int* lst_idx,
+                                               float* lst_val) {
+  if (count > CAP) return false;
+  const int nA = min(K - t0, count);
+  for (int e = threadIdx.x; e < count; e += NT) {
+    const int t = e < nA ? t0 + e : e - nA;
+    const int j = rows.row(t);
+    lst_idx[e] = j;
+    lst_val[e] = rows.coef(t, j);
+  }
+  __syncthreads();
+  return true;
+}
+
 // The row-streaming mat-vec of workgroup g for token b: its share of the (strip, kept row) pairs,
 // at most two segments, each reduced and handed over by reduce_and_finish.  With an index list the
 // workgroup first copies its ranks' (row, coefficient) pairs into LDS (coalesced), so the row loop
@@ -313,17 +335,7 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
   const int f1 = min(f0 + a.chunk, a.nstrips * K);
   Segment sg{f0 / K, 0, 0};
   sg.t0 = f0 - sg.s * K;
-  const bool staged = INDEXED && (f1 - f0) <= kRowListMax;   // uniform over the workgroup
-  if (staged) {
-    const int nA = min(K - sg.t0, f1 - f0);     // entries [0, nA): ranks t0 + e; entries [nA, ..): ranks e - nA
-    for (int e = threadIdx.x; e < f1 - f0; e += RW * 64) {
-      const int t = e < nA ? sg.t0 + e : e - nA;
-      const int j = rows.row(t);
-      lst_idx[e] = j;
-      lst_val[e] = rows.coef(t, j);
-    }
-    __syncthreads();
-  }
+  const bool staged = INDEXED && stage_row_list<RW * 64>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
   int seg_no = 0;
   int list_base = 0;
   while (f0 < f1) {

@@ -66,6 +66,7 @@ __device__ __forceinline__ void stream_rows_w4(const uint32_t* __restrict__ wcol
 constexpr int kW4WideAcc = 32;
 constexpr int kW4WideCols = 64 * kW4WideAcc;
 constexpr int kW4WideUnroll = 8;
+constexpr int kW4WideList = 512;
 
 template <typename T, typename Rows>
 __device__ __forceinline__ void stream_rows_w4_wide(const uint32_t* __restrict__ wcol, int row_dwords,
@@ -110,8 +111,11 @@ __device__ __forceinline__ void stream_rows_w4_wide(const uint32_t* __restrict__
 }
 
 template <typename T, int RW, bool INDEXED>
-__global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
+__global__ __launch_bounds__(RW * 64, 2) void gemv_rows_w4_wide_kernel(W4Args w) {   // two workgroups per CU
   __shared__ GemvShared<RW, kW4WideAcc> sh;
+  // a short list: this kernel's reduction buffers already take 57 KB of LDS per workgroup
+  __shared__ int lst_idx[INDEXED ? kW4WideList : 1];
+  __shared__ float lst_val[INDEXED ? kW4WideList : 1];
   const GemvArgs& a = w.g;
   const int lane = threadIdx.x & 63;
   const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
@@ -130,7 +134,9 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
   const int f1 = min(f0 + a.chunk, a.nstrips * K);
   Segment sg{f0 / K, 0, 0};
   sg.t0 = f0 - sg.s * K;
+  const bool staged = INDEXED && stage_row_list<RW * 64, kW4WideList>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
   int seg_no = 0;
+  int list_base = 0;
   while (f0 < f1) {
     sg.t1 = min(K, sg.t0 + (f1 - f0));
     const int col = sg.s * kW4WideCols + lane * kW4WideAcc;
@@ -141,10 +147,20 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
     const int per = (n + RW - 1) / RW;
     const int ra = sg.t0 + rw * per;
     const int re = min(sg.t1, ra + per);
-    if (col < a.d_out)   // d_out % 32 == 0 in this geometry: the lane's 32 columns are valid together
-      stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+    if (col < a.d_out) {
+      if (staged) {
+        LdsRows lr;
+        lr.idx = lst_idx + list_base;
+        lr.val = lst_val + list_base;
+        lr.base = sg.t0;
+        stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
+      } else {
+        stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+      }
+    }
     reduce_and_finish<T, RW, kW4WideAcc>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep,
                                          sh, lane, rw);
+    list_base += n;
     f0 += sg.t1 - sg.t0;
     sg.s += 1;
     sg.t0 = 0;
@@ -155,6 +171,8 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_wide_kernel(W4Args w) {
 template <typename T, int RW, bool INDEXED>
 __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
   __shared__ GemvShared<RW> sh;
+  __shared__ int lst_idx[INDEXED ? kRowListMax : 1];
+  __shared__ float lst_val[INDEXED ? kRowListMax : 1];
   const GemvArgs& a = w.g;
   const int lane = threadIdx.x & 63;
   const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
@@ -173,7 +191,9 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
   const int f1 = min(f0 + a.chunk, a.nstrips * K);
   Segment sg{f0 / K, 0, 0};
   sg.t0 = f0 - sg.s * K;
+  const bool staged = INDEXED && stage_row_list<RW * 64>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
   int seg_no = 0;
+  int list_base = 0;
   while (f0 < f1) {
     sg.t1 = min(K, sg.t0 + (f1 - f0));
     const int col = sg.s * kStripCols + lane * 8;
@@ -184,10 +204,20 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
     const int per = (n + RW - 1) / RW;
     const int ra = sg.t0 + rw * per;
     const int re = min(sg.t1, ra + per);
-    if (col < a.d_out)
-      stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+    if (col < a.d_out) {
+      if (staged) {
+        LdsRows lr;
+        lr.idx = lst_idx + list_base;
+        lr.val = lst_val + list_base;
+        lr.base = sg.t0;
+        stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
+      } else {
+        stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
+      }
+    }
     reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
                              rw);
+    list_base += n;
     f0 += sg.t1 - sg.t0;
     sg.s += 1;
     sg.t0 = 0;
