@@ -42,20 +42,42 @@ size_t batched_partial_bytes(const GemvPlan& p, int B, bool coef_scale) {
   return groups * tpg * p.partial_floats * sizeof(float);
 }
 
-// One launch of the batched kernels (B > 1): C holds the tokens' coefficients over all rows.
-int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
-  const GemvPlan p = plan_batched(a.d_in, a.d_out, batched_uses_mfma(a.B, a.coef_scale != nullptr));
-  const int tpg = batched_tokens_per_group(a.B, a.coef_scale != nullptr);
+// One launch of the batched kernels (B > 1): C holds the tokens' coefficients over all rows.  An
+// optional side product (side.W != nullptr: same token count, no coefficient scale) shares the launch.
+int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st, BatchArgs side = BatchArgs{}) {
+  const bool cs = a.coef_scale != nullptr;
+  const bool has_side = side.W != nullptr && batched_uses_mfma(a.B, cs);
+  const GemvPlan p = plan_batched(a.d_in, a.d_out, batched_uses_mfma(a.B, cs));
+  const int tpg = batched_tokens_per_group(a.B, cs);
   const size_t groups = (a.B + tpg - 1) / tpg;
-  if (groups * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
-  const size_t need = kCounterBytes + batched_partial_bytes(p, a.B, a.coef_scale != nullptr);
-  if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
+  size_t slots = groups * p.nstrips;
+  size_t pbytes = batched_partial_bytes(p, a.B, cs);
+  unsigned* counters = static_cast<unsigned*>(ws);
+  char* partial = static_cast<char*>(ws) + kCounterBytes;
+  BatchPair pr{};
+  if (has_side) {
+    const GemvPlan ps = plan_batched(side.d_in, side.d_out, true);
+    side.chunk = ps.chunk;
+    side.G = ps.G;
+    side.nstrips = ps.nstrips;
+    side.counters = counters + slots * kCounterStride;
+    side.partial = reinterpret_cast<float*>(partial + pbytes);
+    slots += groups * ps.nstrips;
+    pbytes += batched_partial_bytes(ps, a.B, false);
+    pr.side = side;
+    pr.side_G = ps.G;
+  }
+  if (slots > kCounterSlots) return LAROSA_EUNSUPPORTED;
+  if (!ws || !aligned(ws, 256) || ws_bytes < kCounterBytes + pbytes) return LAROSA_EWORKSPACE;
   a.chunk = p.chunk;
   a.G = p.G;
   a.nstrips = p.nstrips;
-  a.counters = static_cast<unsigned*>(ws);
-  a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
-  return launch_batched(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
+  a.counters = counters;
+  a.partial = reinterpret_cast<float*>(partial);
+  pr.main = a;
+  if (launch_batched_pair(pr, bf16, st) != hipSuccess) return LAROSA_EHIP;
+  if (side.W != nullptr && !has_side) return run_batched(side, bf16, ws, ws_bytes, st);   // FMA path: two launches
+  return LAROSA_OK;
 }
 
 struct Carver {
@@ -279,8 +301,9 @@ static size_t layer_gemv_ws(const larosa_layer* L, int B) {
       const GemvPlan bp[] = {plan_batched(L->d, L->d, m), plan_batched(L->d, L->d_q + 2 * L->d_kv, m),
                              plan_batched(L->d_q, L->d, m), plan_batched(L->d, 2 * L->d_ff, m),
                              plan_batched(L->d_ff, L->d, m)};
+      const size_t side_bytes = (m && (L->shortcut_attn || L->shortcut_mlp)) ? batched_partial_bytes(bp[0], B, false) : 0;
       for (const GemvPlan& p : bp) {
-        const size_t need = round_up(kCounterBytes + batched_partial_bytes(p, B, m ? false : cs), 256);
+        const size_t need = round_up(kCounterBytes + batched_partial_bytes(p, B, m ? false : cs) + side_bytes, 256);
         if (need > s) s = need;
       }
     }
@@ -418,14 +441,22 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   if (B > 1) {
     // Batched decode: per-token Top-K writes each token's activations with the dropped channels
     // zeroed, and one pass over all weight rows serves every token (the union of the index sets).
-    auto project = [&](const void* W, int d_in, int d_out, uint16_t* y, const uint16_t* residual,
-                       uint16_t* y_pre) -> int {
+    // a projection over the masked activations; the shortcut adapter of the block (scA: dst = src scA)
+    // shares its launch
+    auto project = [&](const void* W, int d_in, int d_out, uint16_t* y, const uint16_t* residual, uint16_t* y_pre,
+                       const void* scA = nullptr, const uint16_t* sc_src = nullptr, uint16_t* sc_dst = nullptr) -> int {
       BatchArgs a{};
       a.W = static_cast<const uint16_t*>(W);
       a.C = masked; a.y = y;
       a.d_in = d_in; a.d_out = d_out; a.B = B;
       a.residual = residual; a.y_pre = y_pre;
-      return run_batched(a, bf, ws, gws, st);
+      BatchArgs side{};
+      if (scA) {
+        side.W = static_cast<const uint16_t*>(scA);
+        side.C = sc_src; side.y = sc_dst;
+        side.d_in = d; side.d_out = d; side.B = B;
+      }
+      return run_batched(a, bf, ws, gws, st, side);
     };
     // block input and its select: with an explicit rotation the matrix pass comes first; with the
     // rotation absorbed the pre-norm is formed inside the select kernel
@@ -442,9 +473,8 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       sc.norm_scale = static_cast<const uint16_t*>(scale); sc.norm_eps = L->rms_eps;
       return launch_topk_from(sc, B, d, K, idx, masked, bf, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
     };
-    if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
     LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, idx1, 1));
-    LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr));
+    LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr, L->shortcut_attn, x, s1));
     mark(2);
     {
       TopkSource sc{};
@@ -455,9 +485,8 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     }
     LAROSA_TRY(project(L->Wo, d_q, d, x1, s1 ? s1 : x, o));
     mark(3);
-    if (s2) LAROSA_TRY(shortcut(x1, L->shortcut_mlp, s2));
     LAROSA_TRY(input_and_select(x1, L->Q_mlp, L->rms_mlp, h3, L->K3, idx3, 4));
-    LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr));
+    LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr, L->shortcut_mlp, x1, s2));
     mark(5);
     {
       TopkSource sc{};

@@ -321,7 +321,7 @@ constexpr int kMTileStride = 130;   // floats per token row of an LDS tile (8-by
 // Narrow strips keep the number of workgroups that share a strip -- and with it the partial-sum
 // traffic, which grows with the token count -- small.
 template <typename T, int NTB>
-__global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
+__device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int grp) {
   __shared__ float tile[4][16][kMTileStride];
   __shared__ float scale_s[NTB * 16];
   __shared__ int s_last;
@@ -331,8 +331,6 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
   const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kgrp = lane >> 4;    // K-run of 4 rows inside a 16-row tile
   const int m = lane & 15;       // column group (A operand) / token (B operand)
-  const int g = blockIdx.x;
-  const int grp = blockIdx.y;
   const int b0 = grp * NTB * 16;
   const int K = a.d_in;
   const int chunk = a.chunk;
@@ -537,14 +535,27 @@ __global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchArgs a) {
   }
 }
 
+
+// One launch, up to two independent products: workgroups [0, side_G) of the grid run the side product
+// (a residual adapter on a block's shortcut, which needs only the block's input), the others the main
+// one.  Both use the same token grouping (blockIdx.y).
+template <typename T, int NTB>
+__global__ __launch_bounds__(kBThreads) void skinny_mfma_kernel(BatchPair p) {
+  const int g = blockIdx.x;
+  const bool side = g < p.side_G;                       // uniform over the workgroup
+  skinny_mfma_body<T, NTB>(side ? p.side : p.main, side ? g : g - p.side_G, blockIdx.y);
+}
+
 }  // namespace
 bool batched_uses_mfma(int B, bool coef_scale);
 namespace {
 
 template <typename T>
-hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
+hipError_t launch_batched_t(const BatchPair& p, hipStream_t st) {
+  const BatchArgs& a = p.main;
   const dim3 block(kBThreads);
   if (!batched_uses_mfma(a.B, a.coef_scale != nullptr)) {
+    if (p.side_G > 0) return hipErrorInvalidValue;   // the FMA kernel carries no side product
     // (a per-channel coefficient scale is applied in fp32, which only the FMA kernel does)
     if (a.B <= 2) {
       hipLaunchKernelGGL((skinny_fma_kernel<T, 2>), dim3(a.G, (a.B + 1) / 2), block, 0, st, a);
@@ -552,9 +563,9 @@ hipError_t launch_batched_t(BatchArgs a, hipStream_t st) {
       hipLaunchKernelGGL((skinny_fma_kernel<T, 4>), dim3(a.G, (a.B + 3) / 4), block, 0, st, a);
     }
   } else if (a.B <= 16) {
-    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G, 1), block, 0, st, a);
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G + p.side_G, 1), block, 0, st, p);
   } else {
-    hipLaunchKernelGGL((skinny_mfma_kernel<T, 2>), dim3(a.G, (a.B + 31) / 32), block, 0, st, a);
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 2>), dim3(a.G + p.side_G, (a.B + 31) / 32), block, 0, st, p);
   }
   return hipGetLastError();
 }
@@ -591,7 +602,13 @@ hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C,
 }
 
 hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s) {
-  return bf16 ? launch_batched_t<BF16>(a, s) : launch_batched_t<F16>(a, s);
+  BatchPair p{};
+  p.main = a;
+  return bf16 ? launch_batched_t<BF16>(p, s) : launch_batched_t<F16>(p, s);
+}
+
+hipError_t launch_batched_pair(const BatchPair& p, bool bf16, hipStream_t s) {
+  return bf16 ? launch_batched_t<BF16>(p, s) : launch_batched_t<F16>(p, s);
 }
 
 }  // namespace larosa

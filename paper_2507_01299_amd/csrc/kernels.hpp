@@ -118,6 +118,13 @@ GemvPlan plan_batched(int d_in, int d_out, bool mfma);
 bool batched_uses_mfma(int B, bool coef_scale);
 int batched_tokens_per_group(int B, bool coef_scale);
 hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s);
+// Two independent batched products in one launch of the matrix-core kernel (same token count, no
+// fp32 coefficient scale): the first side_G workgroups of the grid run `side`.
+struct BatchPair {
+  BatchArgs main, side;
+  int side_G;                 // 0: main only
+};
+hipError_t launch_batched_pair(const BatchPair& p, bool bf16, hipStream_t s);
 // C[b,:] = 0 except C[b, idx[b,t]] = h[b, idx[b,t]]
 hipError_t launch_batch_prep(const uint16_t* h, const int32_t* idx, uint16_t* C, int B, int d_in, int K, hipStream_t s);
 
