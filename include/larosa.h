@@ -220,8 +220,11 @@ int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype
  * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,
  * 2: 4), key 3 = decoder layer with the Top-K fused into the projection kernels (1, default) or
  * as separate kernels (0), key 4 = row-waves per workgroup of that fused kernel (8 or 16),
- * key 5 / key 6 = workgroups of a projection / of the shortcut adapter that shares its launch,
- * key 7 = narrowest output width for which the 4-bit projection uses its 2048-column geometry.
+ * key 5 / key 6 = workgroups of a projection / of the shortcut adapter that shares its launch
+ * (0 = chosen from the two jobs' sizes, default),
+ * key 7 = narrowest output width for which the 4-bit projection uses its 2048-column geometry,
+ * key 8 = widest MLP intermediate vector whose Top-K runs inside the down projection's workgroups
+ * (wider ones are selected once by the Top-K kernel).
  * Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 

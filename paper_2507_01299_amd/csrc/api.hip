@@ -14,7 +14,6 @@ constexpr size_t kCounterSlots = 4096;                        // arrival counter
 constexpr size_t kCounterWords = kCounterSlots * kCounterStride;
 constexpr size_t kCounterBytes = kCounterWords * sizeof(unsigned);
 constexpr int kMaxTopkD = 32768;
-constexpr int kFusedMaxWidth = 16384;   // widest block input selected inside every projection workgroup
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -107,18 +106,36 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   return launch_gemv(a, bf16, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
 }
 
+// Workgroups of a projection (main) and of the shortcut adapter that shares its launch, from the
+// two jobs' sizes in strip-rows (512-column pieces of weight rows).  Measured on 7B-, 8B- and 70B-shaped
+// layers: 256 + 192 is best while one workgroup's share stays small; an adapter at least as large as
+// the projection takes half of the 512 resident slots; a projection several times the adapter whose
+// workgroups would each stream more than 1 MiB takes three quarters of them.
+struct SideSplit { int main_g, side_g; };
+SideSplit side_split(int d_out, int K, int side_d) {
+  SideSplit r{256, 192};
+  const long main_T = static_cast<long>((d_out + 511) / 512) * K;
+  const long side_T = static_cast<long>((side_d + 511) / 512) * side_d;
+  if (side_T >= main_T && side_T / 192 > 512) r = {256, 256};
+  else if (main_T >= 4 * side_T && main_T / 256 > 1024) r = {384, 128};
+  if (tuning().side_main_g > 0) r.main_g = tuning().side_main_g;
+  if (tuning().side_g > 0) r.side_g = tuning().side_g;
+  return r;
+}
+
 // One launch of the projection kernel with the Top-K prologue, optionally with a dense side job
 // (a.side.W != nullptr: y_side = x_side * W_side over all rows) in the same grid.
 int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   const bool side = a.side.W != nullptr;
-  const GemvPlan p = plan_fused(a.g.d_out, a.g.K, side ? tuning().side_main_g : 0, a.pair_cols);
+  const SideSplit split = side ? side_split(a.g.d_out, a.g.K, a.side.d_out) : SideSplit{0, 0};
+  const GemvPlan p = plan_fused(a.g.d_out, a.g.K, split.main_g, a.pair_cols);
   size_t slots = static_cast<size_t>(a.g.B) * p.nstrips;
   size_t pfloats = static_cast<size_t>(a.g.B) * p.partial_floats;
   unsigned* counters = static_cast<unsigned*>(ws);
   float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
   a.side_G = 0;
   if (side) {
-    const GemvPlan ps = plan_gemv(a.side.d_out, a.side.K, tuning().side_g);
+    const GemvPlan ps = plan_gemv(a.side.d_out, a.side.K, split.side_g);
     a.side.chunk = ps.chunk;
     a.side.G = ps.G;
     a.side.nstrips = ps.nstrips;
@@ -285,13 +302,17 @@ static size_t layer_gemv_ws(const larosa_layer* L, int B) {
     if (need > s) s = need;
   }
   if (L->shortcut_attn || L->shortcut_mlp) {   // a projection and its shortcut adapter in one launch
-    const GemvPlan side = plan_gemv(L->d, L->d, tuning().side_g);
-    const GemvPlan mains[] = {plan_fused(L->d_q + 2 * L->d_kv, L->K1, tuning().side_main_g),
-                              plan_fused(2 * L->d_ff, L->K3, tuning().side_main_g)};
-    for (const GemvPlan& p : mains) {
-      const size_t need = round_up(
-          kCounterBytes + static_cast<size_t>(B) * (p.partial_floats + side.partial_floats) * sizeof(float), 256);
-      if (need > s) s = need;
+    const int douts[] = {L->d_q + 2 * L->d_kv, 2 * L->d_ff};
+    const int Ks[] = {L->K1, L->K3};
+    for (int i = 0; i < 2; ++i) {
+      const SideSplit split = side_split(douts[i], Ks[i], L->d);
+      const GemvPlan side = plan_gemv(L->d, L->d, split.side_g);
+      for (int pair = 0; pair <= i; ++pair) {     // gate|up also in its paired-strip geometry
+        const GemvPlan p = plan_fused(douts[i], Ks[i], split.main_g, pair ? L->d_ff : 0);
+        const size_t need = round_up(
+            kCounterBytes + static_cast<size_t>(B) * (p.partial_floats + side.partial_floats) * sizeof(float), 256);
+        if (need > s) s = need;
+      }
     }
   }
   if (B > 1) {
@@ -543,7 +564,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2, d_ff,
                      h4));
     mark(5);
-    if (d_ff <= kFusedMaxWidth) {
+    if (d_ff <= tuning().fused_max_width) {
       LAROSA_TRY(fused(kSrcPlain, h4, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
                        nullptr, T.idx4, nullptr));
     } else {
@@ -786,16 +807,20 @@ int larosa_set_tuning(int key, int value) {
       tuning().fused_rw = value;
       return LAROSA_OK;
     case 5:
-      if (value < 8 || value > 2048) return LAROSA_EINVAL;
+      if (value != 0 && (value < 8 || value > 2048)) return LAROSA_EINVAL;
       tuning().side_main_g = value;
       return LAROSA_OK;
     case 6:
-      if (value < 8 || value > 2048) return LAROSA_EINVAL;
+      if (value != 0 && (value < 8 || value > 2048)) return LAROSA_EINVAL;
       tuning().side_g = value;
       return LAROSA_OK;
     case 7:
       if (value < 2048 || value > (1 << 30)) return LAROSA_EINVAL;
       tuning().w4_wide_min_cols = value;
+      return LAROSA_OK;
+    case 8:
+      if (value < 8 || value > kMaxTopkD) return LAROSA_EINVAL;
+      tuning().fused_max_width = value;
       return LAROSA_OK;
     default:
       return LAROSA_EINVAL;

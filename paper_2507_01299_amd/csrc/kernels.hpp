@@ -41,9 +41,10 @@ struct Tuning {
   int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
   int fused_rw = 8;           // row-waves of the fused kernel: 8 (two workgroups per CU) or 16 (one)
-  int side_main_g = 256;      // workgroups of a projection that shares its launch with a shortcut adapter
+  int side_main_g = 0;        // workgroups of a projection that shares its launch with a shortcut adapter; 0 = by size
   int w4_wide_min_cols = 32768;   // 4-bit kernel: narrowest output that uses the 2048-column geometry
-  int side_g = 192;           // workgroups of that adapter (all of both jobs resident at once: 448 of 512 slots)
+  int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
+  int side_g = 0;             // workgroups of that adapter; 0 = by size (both jobs resident at once: at most 512 slots)
 };
 Tuning& tuning();
 

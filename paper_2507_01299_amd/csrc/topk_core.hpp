@@ -4,8 +4,11 @@
 // The ordering key is the stored 16-bit pattern with the sign cleared (15 bits, unsigned), so
 // the selection is pure integer work and identical for binary16 and bfloat16.  Lane t owns the
 // contiguous elements [t*E, (t+1)*E) and keeps them in registers through all phases:
-//   1. 256-bin histogram of the top 8 key bits (one LDS copy per wave to spread atomics);
-//      suffix sums from the top locate the bin holding the K-th largest key;
+//   1. 256-bin histogram of the top 8 key bits.  Activations crowd into a few of these bins (for
+//      bfloat16 the 8 bits are the exponent alone), and lanes of one wave that add to the same LDS
+//      word are served one per clock; so each bin has kTopkCopies words and a lane adds to copy
+//      (lane mod kTopkCopies): at most 64 / kTopkCopies lanes meet in a word whatever the data.
+//      Suffix sums from the top locate the bin holding the K-th largest key;
 //   2. 128-bin histogram of the low 7 bits inside that bin gives the threshold key T and
 //      r = K - #{key > T}, the number of threshold ties to keep;
 //   3. block prefix sums of the ">T" and "==T" counts give every lane the number of kept
@@ -18,10 +21,12 @@
 
 namespace larosa {
 
+constexpr int kTopkCopies = 16;
+
 template <int NW>
 struct TopkShared {
-  unsigned hist_w[NW][256];   // pass 1, one copy per wave
-  unsigned hist2_w[NW][128];  // pass 2 (its own region, so both are cleared in one step)
+  alignas(16) unsigned hist[256 * kTopkCopies];   // pass 1: word bin * kTopkCopies + copy
+  unsigned hist2_w[NW][128];          // pass 2, one copy per wave (adjacent, so both are cleared in one step)
   unsigned wave_tot[NW];
   int bin, bin2;            // pass-1 / pass-2 bin holding the K-th largest key
   unsigned above, above2;   // counts strictly above those bins
@@ -48,15 +53,18 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  unsigned* flat = &sm.hist_w[0][0];   // hist_w and hist2_w are adjacent: NW x 384 words
+  constexpr int kWords = 256 * kTopkCopies + NW * 128;   // hist and hist2_w are adjacent
+  static_assert(offsetof(TopkShared<NW>, hist2_w) == sizeof(unsigned) * 256 * kTopkCopies, "histograms must be adjacent");
+  static_assert(offsetof(TopkShared<NW>, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
 
   // ---- pass 1: top 8 key bits
-  static_assert(offsetof(TopkShared<NW>, hist2_w) == sizeof(unsigned) * NW * 256, "histograms must be adjacent");
-  for (int i = tid; i < NW * 384; i += NT) flat[i] = 0u;
+  uint4* flat = reinterpret_cast<uint4*>(sm.hist);
+  for (int i = tid; i < kWords / 4; i += NT) flat[i] = make_uint4(0u, 0u, 0u, 0u);
   __syncthreads();
+  const unsigned copy = static_cast<unsigned>(lane) & (kTopkCopies - 1);
 #pragma unroll
   for (int q = 0; q < E; ++q)
-    if (q < nvalid) atomicAdd(&sm.hist_w[wave][(raw[q] & 0x7FFFu) >> 7], 1u);
+    if (q < nvalid) atomicAdd(&sm.hist[((raw[q] & 0x7FFFu) >> 7) * kTopkCopies + copy], 1u);
   __syncthreads();
   if (wave == 0) {
     // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p
@@ -64,9 +72,13 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int bin = 255 - (lane * 4 + q);
+      const uint4* w = reinterpret_cast<const uint4*>(sm.hist + bin * kTopkCopies);
       unsigned t = 0;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) t += sm.hist_w[w][bin];
+      for (int k = 0; k < kTopkCopies / 4; ++k) {
+        const uint4 v = w[k];
+        t += (v.x + v.y) + (v.z + v.w);
+      }
       c[q] = t;
       local += t;
     }

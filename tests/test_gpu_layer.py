@@ -207,8 +207,8 @@ def test_shortcut_adapter_launch_shapes(api, side_g, main_g):
         torch.cuda.synchronize()
         check_layer_trace(layers[0], xb, tr, out)
     finally:
-        api.set_tuning(5, 256)
-        api.set_tuning(6, 192)
+        api.set_tuning(5, 0)
+        api.set_tuning(6, 0)
 
 
 @pytest.mark.parametrize("B,form", [(1, "shortcut"), (1, "explicit"), (4, "explicit"), (3, "shortcut")])
