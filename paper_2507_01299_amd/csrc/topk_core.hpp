@@ -6,10 +6,11 @@
 // contiguous elements [t*E, (t+1)*E) and keeps them in registers through all phases:
 //   1. 256-bin histogram of the top 8 key bits.  Activations crowd into a few of these bins (for
 //      bfloat16 the 8 bits are the exponent alone), and lanes of one wave that add to the same LDS
-//      word are served one per clock; so each bin has kTopkCopies words and a lane adds to copy
-//      (lane mod kTopkCopies): at most 64 / kTopkCopies lanes meet in a word whatever the data.
+//      word are served one per clock; so there are kTopkCopies histograms (in different banks for one
+//      bin) and a lane adds to copy (lane mod kTopkCopies): at most 64 / kTopkCopies lanes meet in a
+//      word whatever the data.
 //      Suffix sums from the top locate the bin holding the K-th largest key;
-//   2. 128-bin histogram of the low 7 bits inside that bin gives the threshold key T and
+//   2. 128-bin histogram (same copies) of the low 7 bits inside that bin gives the threshold key T and
 //      r = K - #{key > T}, the number of threshold ties to keep;
 //   3. block prefix sums of the ">T" and "==T" counts give every lane the number of kept
 //      elements before its own, so an index-ordered compaction keeps every key > T and the first
@@ -21,12 +22,14 @@
 
 namespace larosa {
 
-constexpr int kTopkCopies = 16;
+constexpr int kTopkCopies = 8;
+constexpr int kTopkCopyStride = 260;   // words between copies: 16-byte aligned, and the copies of one bin fall in different LDS banks
+constexpr int kTopkCopyStride2 = 132;  // the same for the 128-bin pass
 
 template <int NW>
 struct TopkShared {
-  alignas(16) unsigned hist[256 * kTopkCopies];   // pass 1: word bin * kTopkCopies + copy
-  unsigned hist2_w[NW][128];          // pass 2, one copy per wave (adjacent, so both are cleared in one step)
+  alignas(16) unsigned hist[kTopkCopyStride * kTopkCopies];   // pass 1: word copy * kTopkCopyStride + bin
+  unsigned hist2[kTopkCopyStride2 * kTopkCopies];            // pass 2 (adjacent, so both are cleared in one step)
   unsigned wave_tot[NW];
   int bin, bin2;            // pass-1 / pass-2 bin holding the K-th largest key
   unsigned above, above2;   // counts strictly above those bins
@@ -53,35 +56,30 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  constexpr int kWords = 256 * kTopkCopies + NW * 128;   // hist and hist2_w are adjacent
-  static_assert(offsetof(TopkShared<NW>, hist2_w) == sizeof(unsigned) * 256 * kTopkCopies, "histograms must be adjacent");
+  constexpr int kWords = (kTopkCopyStride + kTopkCopyStride2) * kTopkCopies;   // hist and hist2 are adjacent
+  static_assert(offsetof(TopkShared<NW>, hist2) == sizeof(unsigned) * kTopkCopyStride * kTopkCopies,
+                "histograms must be adjacent");
   static_assert(offsetof(TopkShared<NW>, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
 
   // ---- pass 1: top 8 key bits
   uint4* flat = reinterpret_cast<uint4*>(sm.hist);
   for (int i = tid; i < kWords / 4; i += NT) flat[i] = make_uint4(0u, 0u, 0u, 0u);
   __syncthreads();
-  const unsigned copy = static_cast<unsigned>(lane) & (kTopkCopies - 1);
+  unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride;
 #pragma unroll
   for (int q = 0; q < E; ++q)
-    if (q < nvalid) atomicAdd(&sm.hist[((raw[q] & 0x7FFFu) >> 7) * kTopkCopies + copy], 1u);
+    if (q < nvalid) atomicAdd(&mine[(raw[q] & 0x7FFFu) >> 7], 1u);
   __syncthreads();
   if (wave == 0) {
-    // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p
-    unsigned c[4], local = 0;
+    // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p; its four
+    // counts of one copy are one aligned 16-byte read
+    unsigned c[4] = {0u, 0u, 0u, 0u}, local = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int bin = 255 - (lane * 4 + q);
-      const uint4* w = reinterpret_cast<const uint4*>(sm.hist + bin * kTopkCopies);
-      unsigned t = 0;
-#pragma unroll
-      for (int k = 0; k < kTopkCopies / 4; ++k) {
-        const uint4 v = w[k];
-        t += (v.x + v.y) + (v.z + v.w);
-      }
-      c[q] = t;
-      local += t;
+    for (int k = 0; k < kTopkCopies; ++k) {
+      const uint4 v = *reinterpret_cast<const uint4*>(sm.hist + k * kTopkCopyStride + 252 - 4 * lane);
+      c[0] += v.w; c[1] += v.z; c[2] += v.y; c[3] += v.x;
     }
+    local = (c[0] + c[1]) + (c[2] + c[3]);
     const unsigned need = static_cast<unsigned>(K);
     unsigned run = wave_scan_inclusive(local, lane) - local;
 #pragma unroll
@@ -99,23 +97,21 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   const unsigned above1 = sm.above;
 
   // ---- pass 2: low 7 bits inside bin1
+  unsigned* mine2 = sm.hist2 + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride2;
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&sm.hist2_w[wave][key & 127u], 1u);
+    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&mine2[key & 127u], 1u);
   }
   __syncthreads();
   if (wave == 0) {
-    unsigned c[2], local = 0;
+    unsigned c[2] = {0u, 0u};
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int bin = 127 - (lane * 2 + q);
-      unsigned t = 0;
-#pragma unroll
-      for (int w = 0; w < NW; ++w) t += sm.hist2_w[w][bin];
-      c[q] = t;
-      local += t;
+    for (int k = 0; k < kTopkCopies; ++k) {   // bins 127 - 2*lane (c[0]) and 126 - 2*lane (c[1]): one 8-byte read per copy
+      const uint2 v = *reinterpret_cast<const uint2*>(sm.hist2 + k * kTopkCopyStride2 + 126 - 2 * lane);
+      c[0] += v.y; c[1] += v.x;
     }
+    const unsigned local = c[0] + c[1];
     const unsigned need = static_cast<unsigned>(K) - above1;
     unsigned run = wave_scan_inclusive(local, lane) - local;
 #pragma unroll
