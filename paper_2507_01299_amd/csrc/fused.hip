@@ -45,6 +45,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   const int K = a.g.K;
   const int base = tid * E;
   const int nvalid = max(0, min(E, d_in - base));
+  topk_clear<kFusedRW>(tk);               // made visible by the first barrier below, while the loads are in flight
 
   // ---- the block's input vector, this lane's E elements as stored 16-bit values
   uint16_t raw[E];
@@ -87,6 +88,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
         raw[q] = T::from_f32(xv);
       }
     }
+  } else {
     __syncthreads();
   }
   if (a.h_out && g == 0) {

@@ -23,6 +23,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   const uint16_t* hb = h + static_cast<size_t>(b) * d;
   const int base = threadIdx.x * E;
 
+  topk_clear<kTopkWaves>(sm);             // made visible by the first barrier below
   uint16_t raw[E];
 #pragma unroll
   for (int q = 0; q < E / 4; ++q) {
@@ -72,8 +73,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
     if ((threadIdx.x & 63) == 0) tot_w[threadIdx.x >> 6] = ss;
     __syncthreads();
     float tot = 0.f;
-    for (int w2 = 0; w2 < kTopkWaves; ++w2) tot += tot_w[w2];
-    __syncthreads();                      // wave_tot is reused by the select
+    for (int w2 = 0; w2 < kTopkWaves; ++w2) tot += tot_w[w2];   // the select writes wave_tot only after further barriers
     const float rinv = 1.0f / sqrtf(tot / static_cast<float>(d) + sc.norm_eps);
 #pragma unroll
     for (int q = 0; q < E; ++q) {
@@ -96,6 +96,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
       }
     }
   }
+  if (sc.mode != kSrcNorm) __syncthreads();
   const TopkLane st = block_select<kTopkWaves, E>(raw, nvalid, K, sm);
 
   int32_t* idxb = idx + static_cast<size_t>(b) * K;

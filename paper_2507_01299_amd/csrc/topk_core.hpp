@@ -48,23 +48,28 @@ struct TopkLane {
   __device__ __forceinline__ unsigned end_rank() const { return gt_before + n_gt + min(eq_before + n_eq, r); }
 };
 
-// raw[q] (q < nvalid) are this lane's stored 16-bit values.  Every lane of the NW-wave workgroup
-// must call this.  1 <= K <= total number of valid elements <= 32768.
-template <int NW, int E>
-__device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int nvalid, int K, TopkShared<NW>& sm) {
-  constexpr int NT = NW * 64;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
+// Zero both histograms; every lane of the workgroup calls it.  No barrier: the caller's next barrier
+// (it usually has one of its own while it builds the vector) makes the zeros visible.
+template <int NW>
+__device__ __forceinline__ void topk_clear(TopkShared<NW>& sm) {
   constexpr int kWords = (kTopkCopyStride + kTopkCopyStride2) * kTopkCopies;   // hist and hist2 are adjacent
   static_assert(offsetof(TopkShared<NW>, hist2) == sizeof(unsigned) * kTopkCopyStride * kTopkCopies,
                 "histograms must be adjacent");
   static_assert(offsetof(TopkShared<NW>, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
+  uint4* flat = reinterpret_cast<uint4*>(sm.hist);
+  for (int i = threadIdx.x; i < kWords / 4; i += NW * 64) flat[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// raw[q] (q < nvalid) are this lane's stored 16-bit values.  Every lane of the NW-wave workgroup
+// must call this, after topk_clear and a workgroup barrier.  1 <= K <= total number of valid
+// elements <= 32768.
+template <int NW, int E>
+__device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int nvalid, int K, TopkShared<NW>& sm) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
 
   // ---- pass 1: top 8 key bits
-  uint4* flat = reinterpret_cast<uint4*>(sm.hist);
-  for (int i = tid; i < kWords / 4; i += NT) flat[i] = make_uint4(0u, 0u, 0u, 0u);
-  __syncthreads();
   unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride;
 #pragma unroll
   for (int q = 0; q < E; ++q)
