@@ -146,27 +146,32 @@ def build_folded_stack(shape: synth.LayerShape, n_layers: int, p: float, seed: i
 
 
 def build_shortcut_stack(shape: synth.LayerShape, n_layers: int, p: float, seed: int, n_cal: int,
-                         store: bool = True):
+                         store: bool = True, bases=None):
     """n_layers decoder layers with block-level rotations and residual adapters on the shortcuts
     (Sec. 4.2, Sec. 5.4 "block-level"): layer l's attention block works in the basis Qa_l, its MLP
     block in Qm_l.  q|k|v carry Qa_l^T and gate|up Qm_l^T on the input side; o carries Qm_l and down
     carries Qa_{l+1} on the output side; the stream that skips the attention block goes through
     Qa_l^T Qm_l, the one that skips the MLP block through Qm_l^T Qa_{l+1}.  The stack takes the
     stream in the basis Qa_0 and returns it in the model's own basis (Qa_L = I).  Bases come from PCA
-    of the (normed) block inputs reached by pushing calibration tokens through the dense fp64 stack.
+    of the (normed) block inputs reached by pushing calibration tokens through the dense fp64 stack;
+    bases = (Qa list, Qm list) supplies them instead (any orthogonal matrices give a valid layer: a
+    launch-shape test of a large layer need not pay for its calibration).
     Returns (layers, bits, Qa list, dense weights, source)."""
     dt = shape.dtype if store else None
     src = synth.activation_source(shape.d, seed)
-    X = src.draw(n_cal, seed + 1)
-    Ws, Qa, Qm = [], [], []
-    for l in range(n_layers):
-        W = synth.layer_weights(shape, seed + 100 + 10 * l)
-        Ws.append(W)
-        Qa.append(O.pca_rotation(O.second_moment(O.rmsnorm(X, RMS_EPS)))[0])
-        X1 = _dense_attention_half(X, W, shape, True)
-        Qm.append(O.pca_rotation(O.second_moment(O.rmsnorm(X1, RMS_EPS)))[0])
-        X = dense_layer_reference(W, shape, X)
-    Qa.append(np.eye(shape.d))
+    Ws = [synth.layer_weights(shape, seed + 100 + 10 * l) for l in range(n_layers)]
+    if bases is not None:
+        Qa, Qm = list(bases[0]), list(bases[1])
+        assert len(Qa) == n_layers and len(Qm) == n_layers
+    else:
+        X = src.draw(n_cal, seed + 1)
+        Qa, Qm = [], []
+        for W in Ws:
+            Qa.append(O.pca_rotation(O.second_moment(O.rmsnorm(X, RMS_EPS)))[0])
+            X1 = _dense_attention_half(X, W, shape, True)
+            Qm.append(O.pca_rotation(O.second_moment(O.rmsnorm(X1, RMS_EPS)))[0])
+            X = dense_layer_reference(W, shape, X)
+    Qa.append(None)                       # the stack returns the stream in the model's own basis (identity)
     Ks = (O.kept_count(shape.d, p), O.kept_count(shape.d_q, p),
           O.kept_count(shape.d, p), O.kept_count(shape.d_ff, p))
     layers, bits = [], []
@@ -176,9 +181,10 @@ def build_shortcut_stack(shape: synth.LayerShape, n_layers: int, p: float, seed:
             Wqkv=O.fold_input_side(Qa[l], np.concatenate([W["q"], W["k"], W["v"]], axis=1)),
             Wo=O.fold_output_side(W["o"], Qm[l]),
             Wgu=O.fold_input_side(Qm[l], np.concatenate([W["gate"], W["up"]], axis=1)),
-            Wdown=O.fold_output_side(W["down"], Qa[l + 1]),
+            Wdown=O.fold_output_side(W["down"], Qa[l + 1]) if Qa[l + 1] is not None else W["down"].astype(np.float64),
             shortcut_attn=O.residual_adapter(Qa[l], Qm[l]),
-            shortcut_mlp=O.residual_adapter(Qm[l], Qa[l + 1]))
+            shortcut_mlp=(O.residual_adapter(Qm[l], Qa[l + 1]) if Qa[l + 1] is not None
+                          else np.asarray(Qm[l], np.float64).T.copy()))
         b = {}
         if store:
             for k in list(ops):

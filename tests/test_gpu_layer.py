@@ -328,6 +328,34 @@ def test_config3_llama2_70b_layer_on_one_gpu(api):
     print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
 
 
+def test_config3_llama2_70b_shortcut_form_full_size(api):
+    """The 70B-shaped layer in the form and launch shapes the bench times: rotations absorbed, two
+    8192 x 8192 residual adapters that share the launches of q|k|v (adapter larger than the
+    projection's kept rows: half of the workgroups each) and of gate|up (projection several times the
+    adapter: three quarters of the workgroups), Top-K of the 28672-wide MLP vector in its own kernel.
+    The two bases are seeded random orthogonal matrices (the attention one is the basis planted in the
+    activation source, which PCA of such tokens recovers), so the host pays for the folds only."""
+    shape = synth.SHAPES["llama2-70b"]
+    seed = synth.seed_for(3, 0)
+    print("building llama2-70b shortcut-form case (planted bases, fp64 folds on the host)", flush=True)
+    bases = ([synth.planted_basis(shape.d, seed)], [synth.planted_basis(shape.d, seed + 7)])
+    layers, bits, Qa, Ws, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=seed, n_cal=0, bases=bases)
+    L = layers[0]
+    assert (L.K1, L.K2, L.K3, L.K4) == (4915, 4915, 4915, 17203)
+    case = cases.LayerCase(shape, bits[0], L, {}, src)
+    xb = O.encode16(O.rotate(src.draw(1, synth.seed_for(3, 5)), Qa[0]), shape.dtype)
+    dl = device_layer(case)
+    ws = api.Workspace(dl.workspace_bytes(1))
+    x = to_dev(xb, shape.dtype)
+    out = torch.zeros_like(x)
+    tr = dl.trace_buffers(1)
+    print("running", flush=True)
+    api.layer_forward(dl, x, out, ws, tr)
+    torch.cuda.synchronize()
+    worst = check_layer_trace(L, xb, tr, out)
+    print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
 def test_config4_folded_stack_llama2_7b_shape(api):
     """Deployed form at LLaMA2-7B layer shape: rotations folded (no explicit Q), per-layer adapter as
     a dense 4096 x 4096 mat-vec; a 2-layer slice of the stack, batch 8, every stage of every layer
