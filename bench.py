@@ -750,7 +750,11 @@ def main():
                      "kernel": (("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step "
                                  + ("(two of them carry a residual adapter in the same launch; its bytes are counted), "
                                     if shortcut_form else ", ")
-                                 + ("timed by HIP events around graph replays of the step (= exactly these 4 launches)"
+                                 + (("timed by HIP events around graph replays of the step (= exactly these 4 launches)"
+                                     if shape.d_ff <= 16384 else
+                                     "timed by HIP events around graph replays of the step; the MLP vector is wider than "
+                                     "16384, so its Top-K runs as a kernel of its own in front of the down projection "
+                                     "(5 launches; the step time is still divided by the 4 projections)")
                                     if shortcut_form else "timed by HIP events recorded inside larosa_layer_forward"))
                                 if B == 1 else
                                 "skinny_mfma_kernel: the 4 batched projections of a layer (union of kept rows)"),
