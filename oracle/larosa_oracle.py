@@ -372,18 +372,23 @@ def stage_adapter(L: Layer, x2, dtype):
     return x2 if L.adapter is None else round16(rotate(x2, L.adapter), dtype)
 
 
-def layer_forward(L: Layer, x: np.ndarray, rounded: bool = True) -> dict:
+def layer_forward(L: Layer, x: np.ndarray, rounded: bool = True, attention=None) -> dict:
     """One token through one decoder layer (Fig. 2): h1 -> q|k|v; h2 -> o; h3 -> gate|up;
     h4 = SiLU(gate)*up -> down; residual adds; optional adapter.  With rounded=True every
     tensor that crosses a kernel boundary is rounded to the layer dtype (h1, qkv, h2, o,
     x1, h3, gu, h4, down, x2, x_out); with rounded=False the whole layer is fp64.
+    attention: the attention core, a function q|k|v [d_q + 2 d_kv] -> a [d_q] (the method leaves
+    it unchanged, Sec. 3.1: it only sparsifies its output h2); None = the context-length-1 case.
     Returns every stage in a dict."""
     dt = L.dtype if rounded else None
     x = np.asarray(x, np.float64)
     h1 = block_input(x, L.Q_attn, L.rms_attn, L.rms_eps, dt)
     idx1 = _select(h1, L.K1, dt)
     qkv = stage_qkv(L, h1, idx1, dt)
-    h2 = gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim)
+    if attention is None:
+        h2 = gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim)
+    else:
+        h2 = round16(np.asarray(attention(qkv), np.float64), dt)
     idx2 = _select(h2, L.K2, dt)
     o, x1 = stage_attn_out(L, x, h2, idx2, dt)
     h3 = block_input(x1, L.Q_mlp, L.rms_mlp, L.rms_eps, dt)

@@ -201,10 +201,42 @@ def build_shortcut_stack(shape: synth.LayerShape, n_layers: int, p: float, seed:
     return layers, bits, Qa, Ws, src
 
 
-def dense_layer_reference(W: dict, shape: synth.LayerShape, X: np.ndarray, use_rms: bool = True) -> np.ndarray:
-    """Textbook pre-norm decoder layer at context length 1 in fp64, no rotation, no sparsity:
-    x1 = x + Attn(norm(x)) W_o with Attn = value head of the query head's group;
-    x2 = x1 + (SiLU(n W_gate) * (n W_up)) W_down.  Written without the oracle's layer code."""
+class CachedAttention:
+    """A caller's attention core for tests: grouped-query softmax attention of one new token over a
+    seeded cache of n_ctx earlier (key, value) pairs plus its own, scores q.k / sqrt(head_dim).
+    Plain fp64 numpy, per head, written from the textbook definition; call it with q|k|v of one
+    token ([d_q + 2 d_kv]) to get a [d_q]."""
+
+    def __init__(self, shape: synth.LayerShape, n_ctx: int, seed: int, scale: float = 1.0):
+        rng = np.random.default_rng(seed)
+        self.shape = shape
+        self.k_cache = rng.standard_normal((n_ctx, shape.d_kv)) * scale
+        self.v_cache = rng.standard_normal((n_ctx, shape.d_kv)) * scale
+
+    def __call__(self, qkv: np.ndarray) -> np.ndarray:
+        sh = self.shape
+        hd = sh.head_dim
+        q, k, v = qkv[:sh.d_q], qkv[sh.d_q:sh.d_q + sh.d_kv], qkv[sh.d_q + sh.d_kv:]
+        keys = np.vstack([self.k_cache, k[None, :]])
+        vals = np.vstack([self.v_cache, v[None, :]])
+        group = (sh.d_q // hd) // (sh.d_kv // hd)
+        out = np.empty(sh.d_q)
+        for head in range(sh.d_q // hd):
+            kv = head // group
+            qh = q[head * hd:(head + 1) * hd]
+            scores = keys[:, kv * hd:(kv + 1) * hd] @ qh / np.sqrt(hd)
+            w = np.exp(scores - scores.max())
+            w /= w.sum()
+            out[head * hd:(head + 1) * hd] = w @ vals[:, kv * hd:(kv + 1) * hd]
+        return out
+
+
+def dense_layer_reference(W: dict, shape: synth.LayerShape, X: np.ndarray, use_rms: bool = True,
+                          attention=None) -> np.ndarray:
+    """Textbook pre-norm decoder layer in fp64, no rotation, no sparsity:
+    x1 = x + Attn(norm(x)) W_o, by default at context length 1 (Attn = value head of the query head's
+    group), else attention(q|k|v) per token; x2 = x1 + (SiLU(n W_gate) * (n W_up)) W_down.
+    Written without the oracle's layer code."""
     f = lambda a: a.astype(np.float64)
     X = np.asarray(X, np.float64)
 
@@ -215,7 +247,11 @@ def dense_layer_reference(W: dict, shape: synth.LayerShape, X: np.ndarray, use_r
     v = n @ f(W["v"])
     hd = shape.head_dim
     g = (shape.d_q // hd) // (shape.d_kv // hd)
-    a = np.concatenate([v[..., (i // g) * hd:(i // g + 1) * hd] for i in range(shape.d_q // hd)], axis=-1)
+    if attention is None:
+        a = np.concatenate([v[..., (i // g) * hd:(i // g + 1) * hd] for i in range(shape.d_q // hd)], axis=-1)
+    else:
+        qkv = np.concatenate([n @ f(W["q"]), n @ f(W["k"]), v], axis=-1)
+        a = np.stack([attention(row) for row in qkv.reshape(-1, qkv.shape[-1])]).reshape(X.shape[:-1] + (shape.d_q,))
     x1 = X + a @ f(W["o"])
     n = norm(x1)
     gate = n @ f(W["gate"])

@@ -99,3 +99,36 @@ def test_sparse_layer_is_close_to_dense_and_keeps_exact_counts():
         dense = cases.dense_layer_reference(case.dense["W"], SMALL, x[t])
         rel = np.linalg.norm(r["x_out"] - dense) / np.linalg.norm(dense)
         assert rel < 0.2
+
+
+def test_attention_core_hook_default_and_full_K_dense():
+    """The attention core is the caller's (Sec. 3.1: the method only sparsifies its output h2).  Passing
+    the context-length-1 case explicitly changes nothing; with a softmax attention over a cache, the
+    folded layer at full K, un-rotated, is the textbook dense layer with that attention; and at 40 %
+    sparsity h2 is the attention's rounded output and the later stages are the staged functions of it."""
+    layers, _, Qa, Ws, src = cases.build_shortcut_stack(SMALL, 1, 0.4, seed=77, n_cal=512, store=False)
+    L = layers[0]
+    att = cases.CachedAttention(SMALL, n_ctx=5, seed=3)
+    X = src.draw(2, seed=11)
+    for t in range(2):
+        xt = O.rotate(X[t], Qa[0])
+        a = O.layer_forward(L, xt, rounded=True)
+        b = O.layer_forward(L, xt, rounded=True,
+                            attention=lambda qkv: O.gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim))
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+        r = O.layer_forward(L, xt, rounded=True, attention=att)
+        assert np.array_equal(r["h2"], O.round16(att(r["qkv"]), L.dtype))
+        assert not np.allclose(r["h2"], a["h2"])                      # the cache does change the output
+        assert np.array_equal(r["idx2"], O.topk_indices(O.encode16(r["h2"], L.dtype), L.K2))
+        o, x1 = O.stage_attn_out(L, xt, r["h2"], r["idx2"], L.dtype)
+        assert np.array_equal(r["o"], o) and np.array_equal(r["x1"], x1)
+    _full_K(L)
+    want = cases.dense_layer_reference(Ws[0], SMALL, X, attention=att)
+    for t in range(2):
+        got = O.layer_forward(L, O.rotate(X[t], Qa[0]), rounded=False, attention=att)["x_out"]
+        assert np.max(np.abs(got - want[t])) < 1e-9 * np.max(np.abs(want[t]))
+    # the attention reference itself: with q = 0 every score is equal, so the output is the mean of the values
+    one = cases.CachedAttention(SMALL, n_ctx=1, seed=4)
+    qkv = np.zeros(SMALL.d_q + 2 * SMALL.d_kv)
+    np.testing.assert_allclose(one(qkv)[:SMALL.head_dim], 0.5 * one.v_cache[0, :SMALL.head_dim])
