@@ -111,7 +111,9 @@ typedef struct {
   const void* rms_mlp;        /* [d] or NULL */
   float rms_eps;              /* < 0 disables both pre-norms */
   int attn_mode;              /* 0: context-length-1 attention (softmax over one key = 1, so each query
-                                    head outputs the value head of its group).  No other mode yet. */
+                                    head outputs the value head of its group); must be 0.  A caller with an
+                                    attention core of its own uses larosa_layer_qkv and
+                                    larosa_layer_after_attention instead of larosa_layer_forward. */
   larosa_dtype dtype;
   /* Residual adapters on the two shortcuts (Sec. 4.2; with block-level rotations, Sec. 5.4, there is
    * one per block), each [d,d] or NULL = identity: the stream that skips the attention block is taken
@@ -149,6 +151,24 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B);
  * trace may be NULL.  x_out must not alias x. */
 int larosa_layer_forward(const larosa_layer* L, const void* x, void* x_out, int B,
                          const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
+
+/* The same layer split around the caller's own attention core (KV cache, softmax: the method leaves it
+ * unchanged and only sparsifies its output h2, Sec. 3.1).  Same workspace size, trace and errors as
+ * larosa_layer_forward; each call writes only the trace fields of its own stages.
+ *
+ * larosa_layer_qkv: x [B,d] -> qkv [B, d_q+2*d_kv] = R(S_K1(h1) Wqkv), and, when the layer has
+ * shortcut_attn, s1 [B,d] = R(x shortcut_attn) (required then; ignored and may be NULL otherwise).
+ * trace->qkv and trace->s1 are not written (the caller has both).
+ *
+ * larosa_layer_after_attention: attn [B,d_q] is the attention core's output in the layer dtype and
+ * takes the place of h2; residual [B,d] is what the attention block's output is added to: the layer
+ * input x, or the s1 written by larosa_layer_qkv when the layer has shortcut_attn.  Runs
+ * o = R(S_K2(attn) Wo); x1 = R(residual + o); then the MLP block and the adapter as above.
+ * x_out must not alias residual. */
+int larosa_layer_qkv(const larosa_layer* L, const void* x, void* qkv, void* s1, int B,
+                     const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
+int larosa_layer_after_attention(const larosa_layer* L, const void* residual, const void* attn, void* x_out,
+                                 int B, const larosa_trace* trace, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- Offline part on the GPU (Sec. 4.2: PCA rotation of each layer's input, rotation folded into the
  * neighbouring weights, residual adapter between consecutive layers).  The eigendecomposition itself

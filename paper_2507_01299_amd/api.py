@@ -70,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.larosa_layer_workspace_bytes.restype = sz
         L.larosa_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Layer), i]
         L.larosa_layer_forward.argtypes = [ctypes.POINTER(_Layer), vp, vp, i, ctypes.POINTER(_Trace), vp, sz, vp]
+        L.larosa_layer_qkv.argtypes = [ctypes.POINTER(_Layer), vp, vp, vp, i, ctypes.POINTER(_Trace), vp, sz, vp]
+        L.larosa_layer_after_attention.argtypes = [ctypes.POINTER(_Layer), vp, vp, vp, i, ctypes.POINTER(_Trace), vp,
+                                                   sz, vp]
         L.larosa_set_tuning.argtypes = [i, i]
         L.larosa_quantize_w4.argtypes = [vp, i, i, i, vp, vp, vp]
         L.larosa_sparse_gemv_w4.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
@@ -277,18 +280,44 @@ class Layer:
         return out
 
 
+def _trace_struct(trace: dict | None, stage_events=None):
+    if trace is None and stage_events is None:
+        return None
+    trace = trace or {}
+    tr = _Trace(*[None if trace.get(n) is None else trace[n].data_ptr() for n in TRACE_FIELDS])
+    if stage_events is not None:
+        for i, ev in enumerate(stage_events[:8]):
+            tr.stage_events[i] = None if ev is None else ev.cuda_event
+    return tr
+
+
 def layer_forward(layer: Layer, x, x_out, ws: Workspace, trace: dict | None = None, stage_events=None):
     """stage_events: optional list of up to 8 torch.cuda.Event(enable_timing=True) that have been
     recorded once already (so their handles exist); the library records them at stage boundaries."""
     B = x.shape[0]
-    tr = None
-    if trace is not None or stage_events is not None:
-        trace = trace or {}
-        tr = _Trace(*[None if trace.get(n) is None else trace[n].data_ptr() for n in TRACE_FIELDS])
-        if stage_events is not None:
-            for i, ev in enumerate(stage_events[:8]):
-                tr.stage_events[i] = None if ev is None else ev.cuda_event
+    tr = _trace_struct(trace, stage_events)
     _check(lib().larosa_layer_forward(ctypes.byref(layer.c), _ptr(x), _ptr(x_out), B,
                                       ctypes.byref(tr) if tr is not None else None,
                                       ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_layer_forward")
+    return x_out
+
+
+def layer_qkv(layer: Layer, x, qkv, s1, ws: Workspace, trace: dict | None = None):
+    """First half of the layer for a caller with its own attention core: writes q|k|v and, if the
+    layer has shortcut_attn, the shortcut value s1 (else pass None)."""
+    tr = _trace_struct(trace)
+    _check(lib().larosa_layer_qkv(ctypes.byref(layer.c), _ptr(x), _ptr(qkv), _ptr(s1), x.shape[0],
+                                  ctypes.byref(tr) if tr is not None else None,
+                                  ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_layer_qkv")
+    return qkv
+
+
+def layer_after_attention(layer: Layer, residual, attn, x_out, ws: Workspace, trace: dict | None = None):
+    """Rest of the layer from the attention core's output attn [B, d_q]; residual is the layer input x,
+    or the s1 written by layer_qkv when the layer has shortcut_attn."""
+    tr = _trace_struct(trace)
+    _check(lib().larosa_layer_after_attention(ctypes.byref(layer.c), _ptr(residual), _ptr(attn), _ptr(x_out),
+                                              residual.shape[0], ctypes.byref(tr) if tr is not None else None,
+                                              ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()),
+           "larosa_layer_after_attention")
     return x_out

@@ -346,10 +346,25 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
   return s;
 }
 
-int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, int B, const larosa_trace* tr,
-                         void* ws, size_t ws_bytes, void* stream) {
+namespace {
+
+enum LayerPart { kWholeLayer = 0, kUntilQkv = 1, kAfterAttention = 2 };
+
+// The decoder layer, whole or split around a caller's attention core.  kUntilQkv: q|k|v goes to
+// qkv_ext and the attention shortcut value (if the layer has that adapter) to s1_ext, then the call
+// returns.  kAfterAttention: x_in is the residual of the attention block (the layer input, or that
+// shortcut value) and attn_ext [B, d_q] the attention core's output, which takes the place of h2.
+int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const larosa_trace* tr, void* ws,
+              size_t ws_bytes, void* stream, LayerPart part, void* qkv_ext, void* s1_ext, const void* attn_ext) {
   if (int rc = check_layer(L, B)) return rc;
-  if (!x_in || !x_out || x_in == x_out || !aligned(x_in, 16) || !aligned(x_out, 16)) return LAROSA_EINVAL;
+  if (!x_in || !aligned(x_in, 16)) return LAROSA_EINVAL;
+  if (part == kUntilQkv) {
+    if (!qkv_ext || !aligned(qkv_ext, 16)) return LAROSA_EINVAL;
+    if (L->shortcut_attn && (!s1_ext || !aligned(s1_ext, 16))) return LAROSA_EINVAL;
+  } else {
+    if (!x_out || x_in == x_out || !aligned(x_out, 16)) return LAROSA_EINVAL;
+    if (part == kAfterAttention && (!attn_ext || !aligned(attn_ext, 16))) return LAROSA_EINVAL;
+  }
   if (!ws || !aligned(ws, 256) || ws_bytes < larosa_layer_workspace_bytes(L, B)) return LAROSA_EWORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bool bf = L->dtype == LAROSA_BF16;
@@ -369,7 +384,7 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   static const larosa_trace kNoTrace{};
   const larosa_trace& T = tr ? *tr : kNoTrace;
   uint16_t* h1 = buf16(T.h1, d);
-  uint16_t* qkv = buf16(T.qkv, d_qkv);
+  uint16_t* qkv = part == kUntilQkv ? static_cast<uint16_t*>(qkv_ext) : buf16(T.qkv, d_qkv);
   uint16_t* h2 = buf16(T.h2, d_q);
   uint16_t* o = buf16(T.o, d);
   uint16_t* x1 = buf16(T.x1, d);
@@ -378,7 +393,11 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
   uint16_t* h4 = buf16(T.h4, d_ff);
   uint16_t* down = buf16(T.down, d);
   uint16_t* x2 = L->adapter ? buf16(T.x2, d) : static_cast<uint16_t*>(x_out);
-  uint16_t* s1 = L->shortcut_attn ? buf16(T.s1, d) : nullptr;
+  // after the attention core the shortcut value arrives as x_in, so there is none to compute
+  uint16_t* s1 = !L->shortcut_attn || part == kAfterAttention ? nullptr
+                 : part == kUntilQkv                         ? static_cast<uint16_t*>(s1_ext)
+                                                             : buf16(T.s1, d);
+  const uint16_t* attn = static_cast<const uint16_t*>(attn_ext);
   uint16_t* s2 = L->shortcut_mlp ? buf16(T.s2, d) : nullptr;
   int32_t* idx1 = bufidx(T.idx1, L->K1);
   int32_t* idx2 = bufidx(T.idx2, L->K2);
@@ -494,12 +513,15 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       sc.norm_scale = static_cast<const uint16_t*>(scale); sc.norm_eps = L->rms_eps;
       return launch_topk_from(sc, B, d, K, idx, masked, bf, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
     };
-    LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, idx1, 1));
-    LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr, L->shortcut_attn, x, s1));
-    mark(2);
+    if (part != kAfterAttention) {
+      LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, idx1, 1));
+      LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr, s1 ? L->shortcut_attn : nullptr, x, s1));
+      mark(2);
+      if (part == kUntilQkv) return LAROSA_OK;
+    }
     {
       TopkSource sc{};
-      sc.mode = kSrcGqa; sc.src = qkv; sc.h_out = h2;
+      sc.mode = attn ? kSrcPlain : kSrcGqa; sc.src = attn ? attn : qkv; sc.h_out = h2;
       sc.d_q = d_q; sc.d_kv = d_kv; sc.head_dim = L->head_dim;
       sc.group = (d_q / L->head_dim) / (d_kv / L->head_dim);
       LAROSA_HIP(launch_topk_from(sc, B, d_q, L->K2, idx2, masked, bf, st));
@@ -554,11 +576,14 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
       return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
                    static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst, pair_cols, pair_out);
     };
-    LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1, L->shortcut_attn, s1, 0,
-                     nullptr));
-    mark(2);
-    LAROSA_TRY(fused(kSrcGqa, qkv, L->Wo, x1, d_q, d, L->K2, s1 ? s1 : x, static_cast<uint16_t*>(T.o),
-                     static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
+    if (part != kAfterAttention) {
+      LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1,
+                       s1 ? L->shortcut_attn : nullptr, s1, 0, nullptr));
+      mark(2);
+      if (part == kUntilQkv) return LAROSA_OK;
+    }
+    LAROSA_TRY(fused(attn ? kSrcPlain : kSrcGqa, attn ? attn : qkv, L->Wo, x1, d_q, d, L->K2, s1 ? s1 : x,
+                     static_cast<uint16_t*>(T.o), static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
     mark(3);
     // gate|up with paired strips: the workgroups that finish it also store h4 = R(SiLU(gate) * up)
     LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2, d_ff,
@@ -575,13 +600,18 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
     mark(6);
   } else {
   // attention block: h1 -> q|k|v -> (attention core) -> h2 -> o -> + residual
-  if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
-  LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
-  mark(1);
-  LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, nullptr, st));
-  LAROSA_TRY(sparse(L->Wqkv, h1, idx1, qkv, d, d_qkv, L->K1, nullptr, nullptr));
-  mark(2);
-  LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
+  if (part != kAfterAttention) {
+    if (s1) LAROSA_TRY(shortcut(x, L->shortcut_attn, s1));
+    LAROSA_TRY(block_input(x, L->Q_attn, L->rms_attn, h1));
+    mark(1);
+    LAROSA_HIP(launch_topk(h1, B, d, L->K1, idx1, nullptr, nullptr, st));
+    LAROSA_TRY(sparse(L->Wqkv, h1, idx1, qkv, d, d_qkv, L->K1, nullptr, nullptr));
+    mark(2);
+    if (part == kUntilQkv) return LAROSA_OK;
+    LAROSA_HIP(launch_gqa_expand(qkv, h2, B, d_q, d_kv, L->head_dim, st));
+  } else {
+    LAROSA_HIP(launch_copy_u16(attn, h2, Bz * d_q, st));
+  }
   LAROSA_HIP(launch_topk(h2, B, d_q, L->K2, idx2, nullptr, nullptr, st));
   LAROSA_TRY(sparse(L->Wo, h2, idx2, x1, d_q, d, L->K2, s1 ? s1 : x, o));
   mark(3);
@@ -617,6 +647,23 @@ int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, i
 #undef LAROSA_TRY
 #undef LAROSA_HIP
   return LAROSA_OK;
+}
+
+}  // namespace
+
+int larosa_layer_forward(const larosa_layer* L, const void* x_in, void* x_out, int B, const larosa_trace* tr,
+                         void* ws, size_t ws_bytes, void* stream) {
+  return layer_run(L, x_in, x_out, B, tr, ws, ws_bytes, stream, kWholeLayer, nullptr, nullptr, nullptr);
+}
+
+int larosa_layer_qkv(const larosa_layer* L, const void* x, void* qkv, void* s1, int B, const larosa_trace* tr,
+                     void* ws, size_t ws_bytes, void* stream) {
+  return layer_run(L, x, nullptr, B, tr, ws, ws_bytes, stream, kUntilQkv, qkv, s1, nullptr);
+}
+
+int larosa_layer_after_attention(const larosa_layer* L, const void* residual, const void* attn, void* x_out, int B,
+                                 const larosa_trace* tr, void* ws, size_t ws_bytes, void* stream) {
+  return layer_run(L, residual, x_out, B, tr, ws, ws_bytes, stream, kAfterAttention, nullptr, nullptr, attn);
 }
 
 // ---- offline contractions -------------------------------------------------------------------

@@ -40,10 +40,12 @@ def device_layer(case, device="cuda:0"):
                      shortcut_mlp=to_dev(b.get("shortcut_mlp"), dt, device))
 
 
-def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.Tensor, tol=REL_L2_TOL) -> dict:
+def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.Tensor, tol=REL_L2_TOL,
+                      attn_bits: np.ndarray | None = None) -> dict:
     """Every stage of the GPU trace against the oracle applied to the GPU's own inputs of that
     stage.  Index arrays must be equal; 16-bit tensors within tol relative L2.  Returns the
-    worst relative error per stage."""
+    worst relative error per stage.  attn_bits: the output of a caller's attention core that was
+    handed to the second half of a split layer run; h2 must then be exactly that."""
     dt = L.dtype
     g = {k: (v.cpu().numpy() if k.startswith("idx") else to_bits(v)) for k, v in trace.items() if v is not None}
     g["x_out"] = to_bits(x_out)
@@ -62,7 +64,8 @@ def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.
         h1 = O.decode16(g["h1"][b], dt)
         close("qkv", g["qkv"][b], O.stage_qkv(L, h1, g["idx1"][b], dt))
         qkv = O.decode16(g["qkv"][b], dt)
-        want_h2 = O.encode16(O.gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim), dt)
+        want_h2 = (attn_bits[b] if attn_bits is not None
+                   else O.encode16(O.gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim), dt))
         assert np.array_equal(g["h2"][b], want_h2), "h2"
         assert np.array_equal(g["idx2"][b], O.topk_indices(g["h2"][b], L.K2)), "idx2"
         h2 = O.decode16(g["h2"][b], dt)

@@ -188,6 +188,41 @@ def test_shortcut_adapter_stack_tiny(api, fused_mode, B, dtype):
         cur = out
 
 
+@pytest.mark.parametrize("B", [1, 3])
+@pytest.mark.parametrize("form", ["shortcut", "explicit"])
+def test_layer_split_around_a_callers_attention_core(api, fused_mode, B, form):
+    """larosa_layer_qkv, then softmax attention over a cache computed by the caller (here: fp64 numpy on
+    the GPU's own q|k|v), then larosa_layer_after_attention: every stage equals the oracle's, with h2
+    exactly the caller's vector."""
+    shape = synth.LayerShape("gqa", 1096, 1024, 256, 1160, 64, "bf16")
+    if form == "shortcut":
+        layers, bits, Qa, _, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=81, n_cal=2048)
+        case = cases.LayerCase(shape, bits[0], layers[0], {}, src)
+        xb = O.encode16(O.rotate(src.draw(B, seed=21), Qa[0]), shape.dtype)
+    else:
+        case = cases.build_block_layer(shape, 0.4, seed=82, n_cal=2048)
+        xb, _ = cases.tokens(case, B, 22)
+    L = case.layer
+    print(f"split layer form={form} B={B} mode={fused_mode}", flush=True)
+    dl = device_layer(case)
+    ws = api.Workspace(dl.workspace_bytes(B))
+    x = to_dev(xb, shape.dtype)
+    tr = dl.trace_buffers(B)
+    api.layer_qkv(dl, x, tr["qkv"], tr.get("s1"), ws, tr)
+    torch.cuda.synchronize()
+    att = cases.CachedAttention(shape, n_ctx=7, seed=5, scale=0.05)
+    qkv = O.decode16(to_bits(tr["qkv"]), shape.dtype)
+    attn_bits = O.encode16(np.stack([att(qkv[b]) for b in range(B)]), shape.dtype)
+    out = torch.zeros_like(x)
+    residual = tr["s1"] if L.shortcut_attn is not None else x
+    api.layer_after_attention(dl, residual, to_dev(attn_bits, shape.dtype), out, ws, tr)
+    torch.cuda.synchronize()
+    worst = check_layer_trace(L, xb, tr, out, attn_bits=attn_bits)
+    assert not np.array_equal(attn_bits, O.encode16(O.gqa_single_key_attention(qkv, L.d_q, L.d_kv, L.head_dim),
+                                                    shape.dtype))      # not the built-in stand-in
+    print("worst rel-L2 per stage:", {k: f"{v:.1e}" for k, v in worst.items()}, flush=True)
+
+
 @pytest.mark.parametrize("side_g,main_g", [(256, 256), (64, 448), (512, 512), (8, 16)])
 def test_shortcut_adapter_launch_shapes(api, side_g, main_g):
     """Every split of the shared launch between the projection and its adapter gives the same stages."""

@@ -92,6 +92,22 @@ def test_layer_struct_validation(lib):
     fake = ctypes.c_void_p(0x1000)
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, fake, 1, None, fake, n, None) == api.EINVAL  # x_out aliases x
     assert lib.larosa_layer_forward(ctypes.byref(L), fake, ctypes.c_void_p(0x2000), 1, None, fake, 16, None) == api.EWORKSPACE
+    # the layer split around a caller's attention core
+    other = ctypes.c_void_p(0x2000)
+    assert lib.larosa_layer_qkv(ctypes.byref(L), fake, None, None, 1, None, fake, n, None) == api.EINVAL          # no qkv
+    assert lib.larosa_layer_qkv(ctypes.byref(L), None, other, None, 1, None, fake, n, None) == api.EINVAL
+    assert lib.larosa_layer_qkv(ctypes.byref(L), fake, other, None, 1, None, fake, 16, None) == api.EWORKSPACE
+    L.shortcut_attn = 0x3000
+    n2 = lib.larosa_layer_workspace_bytes(ctypes.byref(L), 2)
+    assert lib.larosa_layer_qkv(ctypes.byref(L), fake, other, None, 1, None, fake, n2, None) == api.EINVAL        # s1 required
+    L.shortcut_attn = None
+    assert lib.larosa_layer_after_attention(ctypes.byref(L), fake, None, other, 1, None, fake, n, None) == api.EINVAL
+    assert lib.larosa_layer_after_attention(ctypes.byref(L), fake, other, fake, 1, None, fake, n, None) == api.EINVAL  # aliasing
+    assert lib.larosa_layer_after_attention(ctypes.byref(L), fake, other, ctypes.c_void_p(0x4000), 1, None, fake, 16,
+                                            None) == api.EWORKSPACE
+    L.attn_mode = 1
+    assert lib.larosa_layer_forward(ctypes.byref(L), fake, other, 1, None, fake, n, None) == api.EUNSUPPORTED
+    L.attn_mode = 0
 
 
 def test_offline_calls_reject_invalid_arguments(lib):
