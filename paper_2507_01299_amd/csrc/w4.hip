@@ -25,6 +25,22 @@ constexpr int kW4Group = 128;
 
 __device__ __forceinline__ uint32_t load_stream4(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 
+// acc[k] += c * q_k for the 8 codes of one dword.  (v >> 4k) & 0x000F000F leaves codes k and k + 4 in
+// the two 16-bit halves of a register; read as binary16 each half is the subnormal q * 2^-24 exactly,
+// and the mixed-precision FMA takes it straight from the register half with the coefficient (scaled
+// by 2^24, exact) and the sum in fp32: two instructions per code instead of extract + convert + FMA.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+constexpr float kW4CodeScale = 16777216.0f;   // 2^24
+
+__device__ __forceinline__ void fma_codes8(uint32_t v, float c_scaled, float* acc) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f16x2 p = __builtin_bit_cast(f16x2, (v >> (4 * k)) & 0x000F000Fu);
+    acc[k] = fmaf(static_cast<float>(p.x), c_scaled, acc[k]);
+    acc[k + 4] = fmaf(static_cast<float>(p.y), c_scaled, acc[k + 4]);
+  }
+}
+
 template <typename T, typename Rows>
 __device__ __forceinline__ void stream_rows_w4(const uint32_t* __restrict__ wcol, int row_dwords,
                                                const uint16_t* __restrict__ scol, int ng, const Rows& rows, int ra,
@@ -46,16 +62,7 @@ __device__ __forceinline__ void stream_rows_w4(const uint32_t* __restrict__ wcol
       float c = rows.coef(min(t + u, re - 1), j[u]) * T::to_f32(s[u]);
       c = (t + u < re) ? c : 0.f;
       csum += c;
-      const uint32_t lo = v[u] & 0x0F0F0F0Fu;          // nibbles 0, 2, 4, 6 as bytes
-      const uint32_t hi = (v[u] >> 4) & 0x0F0F0F0Fu;   // nibbles 1, 3, 5, 7
-      acc[0] = fmaf(c, static_cast<float>(lo & 0xFFu), acc[0]);
-      acc[1] = fmaf(c, static_cast<float>(hi & 0xFFu), acc[1]);
-      acc[2] = fmaf(c, static_cast<float>((lo >> 8) & 0xFFu), acc[2]);
-      acc[3] = fmaf(c, static_cast<float>((hi >> 8) & 0xFFu), acc[3]);
-      acc[4] = fmaf(c, static_cast<float>((lo >> 16) & 0xFFu), acc[4]);
-      acc[5] = fmaf(c, static_cast<float>((hi >> 16) & 0xFFu), acc[5]);
-      acc[6] = fmaf(c, static_cast<float>(lo >> 24), acc[6]);
-      acc[7] = fmaf(c, static_cast<float>(hi >> 24), acc[7]);
+      fma_codes8(v[u], c * kW4CodeScale, acc);
     }
   }
 #pragma unroll
@@ -77,33 +84,26 @@ __device__ __forceinline__ void stream_rows_w4_wide(const uint32_t* __restrict__
   for (int t = ra; t < re; t += kW4WideUnroll) {
     int j[kW4WideUnroll];
     u32x4 v[kW4WideUnroll];
-    uint16_t s[kW4WideUnroll];
+    uint32_t s[kW4WideUnroll];
 #pragma unroll
     for (int u = 0; u < kW4WideUnroll; ++u) j[u] = rows.row(min(t + u, re - 1));
 #pragma unroll
-    for (int u = 0; u < kW4WideUnroll; ++u) {
+    for (int u = 0; u < kW4WideUnroll; ++u) s[u] = scol[static_cast<size_t>(j[u]) * ng];
+#pragma unroll
+    for (int u = 0; u < kW4WideUnroll; ++u)
       v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wcol + static_cast<size_t>(j[u]) * row_dwords));
-      s[u] = scol[static_cast<size_t>(j[u]) * ng];
-    }
+    // All scales must be in registers here.  Without this the compiler sinks each scale load to its
+    // use and waits for it there: one memory round trip per row instead of one per batch of rows.
+#pragma unroll
+    for (int u = 0; u < kW4WideUnroll; ++u) asm volatile("" : "+v"(s[u]));
 #pragma unroll
     for (int u = 0; u < kW4WideUnroll; ++u) {
-      float c = rows.coef(min(t + u, re - 1), j[u]) * T::to_f32(s[u]);
+      float c = rows.coef(min(t + u, re - 1), j[u]) * T::to_f32(static_cast<uint16_t>(s[u]));
       c = (t + u < re) ? c : 0.f;
       csum += c;
+      const float cs = c * kW4CodeScale;
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        const uint32_t lo = v[u][m] & 0x0F0F0F0Fu;
-        const uint32_t hi = (v[u][m] >> 4) & 0x0F0F0F0Fu;
-        float* a8 = acc + m * 8;
-        a8[0] = fmaf(c, static_cast<float>(lo & 0xFFu), a8[0]);
-        a8[1] = fmaf(c, static_cast<float>(hi & 0xFFu), a8[1]);
-        a8[2] = fmaf(c, static_cast<float>((lo >> 8) & 0xFFu), a8[2]);
-        a8[3] = fmaf(c, static_cast<float>((hi >> 8) & 0xFFu), a8[3]);
-        a8[4] = fmaf(c, static_cast<float>((lo >> 16) & 0xFFu), a8[4]);
-        a8[5] = fmaf(c, static_cast<float>((hi >> 16) & 0xFFu), a8[5]);
-        a8[6] = fmaf(c, static_cast<float>(lo >> 24), a8[6]);
-        a8[7] = fmaf(c, static_cast<float>(hi >> 24), a8[7]);
-      }
+      for (int m = 0; m < 4; ++m) fma_codes8(v[u][m], cs, acc + m * 8);
     }
   }
 #pragma unroll
