@@ -68,6 +68,13 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   }
   if (a.src_mode == kSrcNorm) {
     // h = R(x * rsqrt(mean(x^2) + eps) * scale)
+    // the lane's slice of the learned scale, fetched with x (loads at each use would each wait for memory)
+    uint2 sc2[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+      const int i = base + q * 4;
+      sc2[q] = (a.norm_scale && i < d_in) ? *reinterpret_cast<const uint2*>(a.norm_scale + i) : make_uint2(0u, 0u);
+    }
     float ss = 0.f;
 #pragma unroll
     for (int q = 0; q < E; ++q) {
@@ -84,7 +91,8 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
     for (int q = 0; q < E; ++q) {
       if (q < nvalid) {
         float xv = T::to_f32(raw[q]) * rinv;
-        if (a.norm_scale) xv *= T::to_f32(a.norm_scale[base + q]);
+        const uint32_t w = (q & 2) ? sc2[q >> 2].y : sc2[q >> 2].x;
+        if (a.norm_scale) xv *= T::to_f32(static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu)));
         raw[q] = T::from_f32(xv);
       }
     }

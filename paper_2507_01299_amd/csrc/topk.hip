@@ -62,6 +62,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   const int nvalid = max(0, min(E, d - base));
   if (sc.mode == kSrcNorm) {
     // h = R(x * rsqrt(mean(x^2) + eps) * scale): the pre-norm of a block whose rotation is absorbed
+    // the lane's slice of the learned scale, fetched up front (loads at each use would each wait for memory)
+    uint2 sc2[E / 4];
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q) {
+      const int i = base + q * 4;
+      sc2[q] = (sc.norm_scale && i < d) ? *reinterpret_cast<const uint2*>(sc.norm_scale + i) : make_uint2(0u, 0u);
+    }
     float ss = 0.f;
 #pragma unroll
     for (int q = 0; q < E; ++q) {
@@ -79,7 +86,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
     for (int q = 0; q < E; ++q) {
       if (q < nvalid) {
         float xv = T::to_f32(raw[q]) * rinv;
-        if (sc.norm_scale) xv *= T::to_f32(sc.norm_scale[base + q]);
+        const uint32_t w = (q & 2) ? sc2[q >> 2].y : sc2[q >> 2].x;
+        if (sc.norm_scale) xv *= T::to_f32(static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu)));
         raw[q] = T::from_f32(xv);
       }
     }
