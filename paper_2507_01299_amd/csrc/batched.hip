@@ -365,22 +365,27 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
         // first of this lane's 4 rows; t0 % 8 == 0, so j0 % 4 == 0.  A tile past this wave's run
         // starts at t1: its rows clamp to a valid address and its B operand is zero.
         const int j0 = (tl + h2 < tl1) ? t0 + (tl + h2) * 16 + 4 * kgrp : t1;
+        // Every load is unconditional, from an address clamped into the operand (columns past d_out
+        // read the strip's first column, tokens past B the last token, rows past t1 a valid row), and
+        // what must not count is zeroed afterwards: a load under a lane condition sits in a branch of
+        // its own, and the compiler then waits for the earlier loads half-way through issuing them.
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int r = min(j0 + q, t1 - 1);
-          v[h2][q] = colv ? load_stream16(a.W + static_cast<size_t>(r) * a.d_out + colbase) : make_uint4(0u, 0u, 0u, 0u);
+          v[h2][q] = load_stream16(a.W + static_cast<size_t>(r) * a.d_out + (colv ? colbase : s * kMStrip));
         }
         // B operand: 4 consecutive rows of token (b0 + tb*16 + m); rows at or past t1 belong to
         // another workgroup (or do not exist) and must contribute nothing
 #pragma unroll
         for (int tb = 0; tb < NTB; ++tb) {
           const int tok = b0 + tb * 16 + m;
-          uint2 c = make_uint2(0u, 0u);
-          if (tok < a.B && j0 < t1) c = *reinterpret_cast<const uint2*>(a.C + static_cast<size_t>(tok) * K + j0);
+          // j0 % 4 == 0 and K % 8 == 0, so min(j0, K - 4) keeps the four rows inside the token's vector
+          uint2 c = *reinterpret_cast<const uint2*>(a.C + static_cast<size_t>(min(tok, a.B - 1)) * K + min(j0, K - 4));
           if (j0 + 1 >= t1) c.x &= 0x0000FFFFu;
           if (j0 + 2 >= t1) c.y = 0u;
           if (j0 + 3 >= t1) c.y &= 0x0000FFFFu;
-          if (j0 >= t1) c.x = 0u;
+          if (j0 >= t1 || tok >= a.B) c.x = 0u;
+          if (tok >= a.B) c.y = 0u;
           bf[h2][tb] = c;
         }
       }
