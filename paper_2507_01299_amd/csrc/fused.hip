@@ -36,7 +36,8 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   int g = blockIdx.x;
   if (a.side_G > 0) {                     // uniform over the workgroup
     if (g < a.side_G) {
-      gemv_rows_body<T, RW, false>(a.side, g, b, sh);
+      static_assert(kFusedChunkMax >= kRowListMax, "the side job stages its coefficients in lst_val");
+      gemv_rows_body<T, RW, false>(a.side, g, b, sh, nullptr, lst_val);
       return;
     }
     g -= a.side_G;

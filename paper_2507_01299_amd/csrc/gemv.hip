@@ -16,7 +16,9 @@ namespace {
 template <typename T, int RW, bool INDEXED>
 __global__ __launch_bounds__(RW * 64) void gemv_rows_kernel(GemvArgs a) {
   __shared__ GemvShared<RW> sh;
-  gemv_rows_body<T, RW, INDEXED>(a, blockIdx.x, blockIdx.y, sh);
+  __shared__ int lst_idx[INDEXED ? kRowListMax : 1];
+  __shared__ float lst_val[kRowListMax];
+  gemv_rows_body<T, RW, INDEXED>(a, blockIdx.x, blockIdx.y, sh, lst_idx, lst_val);
 }
 
 template <typename T, int RW>

@@ -46,6 +46,14 @@ struct LdsRows {
   __device__ __forceinline__ float coef(int t, int) const { return val[t - base]; }
 };
 
+// The identity row list with its coefficients staged in LDS (dense mat-vec: row t is rank t).
+struct LdsCoefs {
+  const float* val;
+  int base;                  // rank of entry 0
+  __device__ __forceinline__ int row(int t) const { return t; }
+  __device__ __forceinline__ float coef(int t, int) const { return val[t - base]; }
+};
+
 // acc[k] += sum over ranks t in [ra, re) of coef(t) * W[row(t), col + k]
 template <typename T, typename Rows>
 __device__ __forceinline__ void stream_rows(const uint16_t* __restrict__ wcol, int d_out, const Rows& rows, int ra,
@@ -306,7 +314,7 @@ __device__ __forceinline__ bool stage_row_list(const Rows& rows, int t0, int cou
   for (int e = threadIdx.x; e < count; e += NT) {
     const int t = e < nA ? t0 + e : e - nA;
     const int j = rows.row(t);
-    lst_idx[e] = j;
+    if (lst_idx) lst_idx[e] = j;          // the identity list needs no indices
     lst_val[e] = rows.coef(t, j);
   }
   __syncthreads();
@@ -314,13 +322,14 @@ __device__ __forceinline__ bool stage_row_list(const Rows& rows, int t0, int cou
 }
 
 // The row-streaming mat-vec of workgroup g for token b: its share of the (strip, kept row) pairs,
-// at most two segments, each reduced and handed over by reduce_and_finish.  With an index list the
-// workgroup first copies its ranks' (row, coefficient) pairs into LDS (coalesced), so the row loop
-// has no dependent index -> activation -> address chain through global memory.
+// at most two segments, each reduced and handed over by reduce_and_finish.  The workgroup first
+// copies its ranks' (row, coefficient) pairs into LDS (coalesced; lst_idx / lst_val hold kRowListMax
+// entries, the dense form uses only lst_val), so the row loop has no dependent index -> activation
+// -> address chain through global memory, and no per-row activation load that the compiler would
+// wait for row by row.
 template <typename T, int RW, bool INDEXED>
-__device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, GemvShared<RW>& sh) {
-  __shared__ int lst_idx[INDEXED ? kRowListMax : 1];
-  __shared__ float lst_val[INDEXED ? kRowListMax : 1];
+__device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, GemvShared<RW>& sh, int* lst_idx,
+                                               float* lst_val) {
   const int lane = threadIdx.x & 63;
   const int rw = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
   const int K = a.K;
@@ -335,7 +344,7 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
   const int f1 = min(f0 + a.chunk, a.nstrips * K);
   Segment sg{f0 / K, 0, 0};
   sg.t0 = f0 - sg.s * K;
-  const bool staged = INDEXED && stage_row_list<RW * 64>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
+  const bool staged = stage_row_list<RW * 64>(rows, sg.t0, f1 - f0, K, INDEXED ? lst_idx : nullptr, lst_val);
   int seg_no = 0;
   int list_base = 0;
   while (f0 < f1) {
@@ -350,12 +359,17 @@ __device__ __forceinline__ void gemv_rows_body(const GemvArgs& a, int g, int b, 
     const int ra = sg.t0 + rw * per;
     const int re = min(sg.t1, ra + per);
     if (col < a.d_out) {
-      if (staged) {
+      if (staged && INDEXED) {
         LdsRows lr;
         lr.idx = lst_idx + list_base;
         lr.val = lst_val + list_base;
         lr.base = sg.t0;
         stream_rows<T>(a.W + col, a.d_out, lr, ra, re, acc);
+      } else if (staged) {
+        LdsCoefs lc;
+        lc.val = lst_val + list_base;
+        lc.base = sg.t0;
+        stream_rows<T>(a.W + col, a.d_out, lc, ra, re, acc);
       } else {
         stream_rows<T>(a.W + col, a.d_out, rows, ra, re, acc);
       }
