@@ -24,36 +24,55 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
   const int base = threadIdx.x * E;
 
   topk_clear<kTopkWaves>(sm);             // made visible by the first barrier below
+  // All of the lane's loads are issued first, unconditionally and from addresses clamped into the
+  // vector (d % 4 == 0: a group of four is all valid or all past the end; groups past the end re-read
+  // the last group and are ignored).  Loads under a lane or mode condition sit in branches of their
+  // own, and each is then waited for before the next is issued: one memory round trip per group.
+  uint2 ld0[E / 4], ld1[E / 4];
+  if (sc.mode == kSrcGqa) {
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q) {
+      const int i = min(base + q * 4, d - 4);
+      const int head = i / sc.head_dim;
+      const int src = (head / sc.group) * sc.head_dim + (i - head * sc.head_dim);
+      ld0[q] = *reinterpret_cast<const uint2*>(sc.src + static_cast<size_t>(b) * (sc.d_q + 2 * sc.d_kv) + sc.d_q +
+                                               sc.d_kv + src);
+      ld1[q] = make_uint2(0u, 0u);
+    }
+  } else if (sc.mode == kSrcSilu) {
+    const uint16_t* gb = sc.src + static_cast<size_t>(b) * 2 * d;
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q) {
+      const int i = min(base + q * 4, d - 4);
+      ld0[q] = *reinterpret_cast<const uint2*>(gb + i);
+      ld1[q] = *reinterpret_cast<const uint2*>(gb + d + i);
+    }
+  } else {
+#pragma unroll
+    for (int q = 0; q < E / 4; ++q) {
+      ld0[q] = *reinterpret_cast<const uint2*>(hb + min(base + q * 4, d - 4));
+      ld1[q] = make_uint2(0u, 0u);
+    }
+  }
   uint16_t raw[E];
 #pragma unroll
   for (int q = 0; q < E / 4; ++q) {
     const int i = base + q * 4;
-    uint2 v = make_uint2(0u, 0u);
-    if (i < d) {                                                // d % 4 == 0: all four valid or none
-      if (sc.mode == kSrcGqa) {
-        const int head = i / sc.head_dim;
-        const int src = (head / sc.group) * sc.head_dim + (i - head * sc.head_dim);
-        v = *reinterpret_cast<const uint2*>(sc.src + static_cast<size_t>(b) * (sc.d_q + 2 * sc.d_kv) + sc.d_q +
-                                            sc.d_kv + src);
-      } else if (sc.mode == kSrcSilu) {
-        const uint16_t* gb = sc.src + static_cast<size_t>(b) * 2 * d;
-        const uint2 g2 = *reinterpret_cast<const uint2*>(gb + i);
-        const uint2 u2 = *reinterpret_cast<const uint2*>(gb + d + i);
-        float g[4], u[4];
-        T::unpack2(g2.x, g[0], g[1]);
-        T::unpack2(g2.y, g[2], g[3]);
-        T::unpack2(u2.x, u[0], u[1]);
-        T::unpack2(u2.y, u[2], u[3]);
-        uint16_t o[4];
+    uint2 v = ld0[q];
+    if (sc.mode == kSrcSilu) {
+      float g[4], u[4];
+      T::unpack2(ld0[q].x, g[0], g[1]);
+      T::unpack2(ld0[q].y, g[2], g[3]);
+      T::unpack2(ld1[q].x, u[0], u[1]);
+      T::unpack2(ld1[q].y, u[2], u[3]);
+      uint16_t o[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = T::from_f32(silu_f32(g[k]) * u[k]);
-        v.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
-        v.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
-      } else {
-        v = *reinterpret_cast<const uint2*>(hb + i);
-      }
-      if (sc.h_out && sc.mode != kSrcNorm) *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
+      for (int k = 0; k < 4; ++k) o[k] = T::from_f32(silu_f32(g[k]) * u[k]);
+      v.x = o[0] | (static_cast<uint32_t>(o[1]) << 16);
+      v.y = o[2] | (static_cast<uint32_t>(o[3]) << 16);
     }
+    if (i >= d) v = make_uint2(0u, 0u);
+    if (i < d && sc.h_out && sc.mode != kSrcNorm) *reinterpret_cast<uint2*>(sc.h_out + static_cast<size_t>(b) * d + i) = v;
     raw[q * 4 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu);
     raw[q * 4 + 1] = static_cast<uint16_t>(v.x >> 16);
     raw[q * 4 + 2] = static_cast<uint16_t>(v.y & 0xFFFFu);
