@@ -60,9 +60,12 @@ __device__ __forceinline__ void topk_clear(TopkShared<NW>& sm) {
   for (int i = threadIdx.x; i < kWords / 4; i += NW * 64) flat[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
-// raw[q] (q < nvalid) are this lane's stored 16-bit values.  Every lane of the NW-wave workgroup
-// must call this, after topk_clear and a workgroup barrier.  1 <= K <= total number of valid
-// elements <= 32768.
+// raw[q] (q < nvalid) are this lane's stored 16-bit values; raw[q] for q >= nvalid (positions past
+// the end of the vector) MUST be zero.  Such padding is counted like a zero at an index above every
+// real element: it is never above the threshold, and among threshold ties the lower-index rule takes
+// the real elements first (K is at most their number), so it is never kept -- and the three passes
+// over the elements need no per-element predicate.  Every lane of the NW-wave workgroup must call
+// this, after topk_clear and a workgroup barrier.  1 <= K <= total number of valid elements <= 32768.
 template <int NW, int E>
 __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int nvalid, int K, TopkShared<NW>& sm) {
   const int tid = threadIdx.x;
@@ -73,7 +76,7 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride;
 #pragma unroll
   for (int q = 0; q < E; ++q)
-    if (q < nvalid) atomicAdd(&mine[(raw[q] & 0x7FFFu) >> 7], 1u);
+    atomicAdd(&mine[(raw[q] & 0x7FFFu) >> 7], 1u);
   __syncthreads();
   if (wave == 0) {
     // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p; its four
@@ -106,7 +109,7 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    if (q < nvalid && static_cast<int>(key >> 7) == bin1) atomicAdd(&mine2[key & 127u], 1u);
+    if (static_cast<int>(key >> 7) == bin1) atomicAdd(&mine2[key & 127u], 1u);
   }
   __syncthreads();
   if (wave == 0) {
@@ -139,11 +142,10 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    if (q < nvalid) {
-      m_gt |= static_cast<unsigned long long>(key > out.T ? 1u : 0u) << q;
-      m_eq |= static_cast<unsigned long long>(key == out.T ? 1u : 0u) << q;
-    }
+    m_gt |= static_cast<unsigned long long>(key > out.T ? 1u : 0u) << q;
+    m_eq |= static_cast<unsigned long long>(key == out.T ? 1u : 0u) << q;
   }
+  (void)nvalid;
   const unsigned n_gt = static_cast<unsigned>(__popcll(m_gt)), n_eq = static_cast<unsigned>(__popcll(m_eq));
   out.m_gt = m_gt;
   out.m_eq = m_eq;
