@@ -90,12 +90,10 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
     const float rinv = 1.0f / sqrtf(tot / static_cast<float>(d_in) + a.norm_eps);
 #pragma unroll
     for (int q = 0; q < E; ++q) {
-      {
-        float xv = T::to_f32(raw[q]) * rinv;
-        const uint32_t w = (q & 2) ? sc2[q >> 2].y : sc2[q >> 2].x;
-        if (a.norm_scale) xv *= T::to_f32(static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu)));
-        raw[q] = (q < nvalid) ? T::from_f32(xv) : static_cast<uint16_t>(0);   // padding stays zero
-      }
+      float xv = T::to_f32(raw[q]) * rinv;
+      const uint32_t w = (q & 2) ? sc2[q >> 2].y : sc2[q >> 2].x;
+      if (a.norm_scale) xv *= T::to_f32(static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu)));
+      raw[q] = (q < nvalid) ? T::from_f32(xv) : static_cast<uint16_t>(0);   // padding stays zero
     }
   } else {
     __syncthreads();
