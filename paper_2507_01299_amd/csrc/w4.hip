@@ -28,7 +28,9 @@ __device__ __forceinline__ uint32_t load_stream4(const uint32_t* p) { return __b
 // acc[k] += c * q_k for the 8 codes of one dword.  (v >> 4k) & 0x000F000F leaves codes k and k + 4 in
 // the two 16-bit halves of a register; read as binary16 each half is the subnormal q * 2^-24 exactly,
 // and the mixed-precision FMA takes it straight from the register half with the coefficient (scaled
-// by 2^24, exact) and the sum in fp32: two instructions per code instead of extract + convert + FMA.
+// by 2^24, exact unless |coefficient| exceeds 2^104, far beyond any activation times scale) and the sum in
+// fp32: two instructions per code instead of extract + convert + FMA.  Needs binary16 subnormals kept
+// (the default float mode of a HIP kernel), which the parity tests would show at once if it were off.
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 constexpr float kW4CodeScale = 16777216.0f;   // 2^24
 
