@@ -94,6 +94,21 @@ int larosa_sparse_gemv(const void* Wp, const void* h, const int32_t* idx, void* 
                        int B, int d_in, int d_out, int K, larosa_dtype t,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* larosa_sparse_gemv for callers that cannot allocate device memory or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without `ws`, same kernels, same result bit for bit.  The arrival counters and partial strips
+ * live in a device array of LAROSA_STATIC_SCRATCH_BYTES inside the library (one copy per GPU,
+ * held until the process ends); the call allocates and frees nothing.  A request whose scratch
+ * need exceeds that size returns LAROSA_EUNSUPPORTED and enqueues nothing (batch 1 always fits
+ * for d_out <= 262144; for B > 1 the need is that of larosa_workspace_bytes(B, d_in, d_out, K)).
+ * The array's address is looked up on the first call on each device (a host-side query, no
+ * stream work).  The counters are zeroed by a fill kernel at the start of every call, so the
+ * state a previous call left is irrelevant; every call on one GPU shares the one array, so two
+ * calls that overlap on that GPU (different streams) race: order them on one stream. */
+#define LAROSA_STATIC_SCRATCH_BYTES (8u << 20)
+int larosa_sparse_gemv_static(const void* Wp, const void* h, const int32_t* idx, void* y,
+                              int B, int d_in, int d_out, int K, larosa_dtype t, void* stream);
+
 /* One decoder layer (Fig. 2; Sec. 3.1 for h1..h4; Sec. 4.2-4.3).  All pointers device, borrowed
  * for the duration of the call. */
 typedef struct {

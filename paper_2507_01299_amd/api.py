@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.larosa_dense_gemv.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
         L.larosa_topk.argtypes = [vp, i, i, i, vp, vp, i, vp, sz, vp]
         L.larosa_sparse_gemv.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+        L.larosa_sparse_gemv_static.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp]
         L.larosa_layer_workspace_bytes.restype = sz
         L.larosa_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Layer), i]
         L.larosa_layer_forward.argtypes = [ctypes.POINTER(_Layer), vp, vp, i, ctypes.POINTER(_Trace), vp, sz, vp]
@@ -172,6 +173,16 @@ def sparse_gemv(Wp, h, idx, y, dtype, ws: Workspace):
     K = idx.shape[1]
     _check(lib().larosa_sparse_gemv(_ptr(Wp), _ptr(h), _ptr(idx), _ptr(y), B, d_in, d_out, K, dtype_code(dtype),
                                     ctypes.c_void_p(ws.ptr), ws.nbytes, _stream()), "larosa_sparse_gemv")
+    return y
+
+
+def sparse_gemv_static(Wp, h, idx, y, dtype):
+    """larosa_sparse_gemv without a workspace: the scratch is a fixed device array inside the library."""
+    B, d_in = h.shape
+    d_out = Wp.shape[1]
+    K = idx.shape[1]
+    _check(lib().larosa_sparse_gemv_static(_ptr(Wp), _ptr(h), _ptr(idx), _ptr(y), B, d_in, d_out, K,
+                                           dtype_code(dtype), _stream()), "larosa_sparse_gemv_static")
     return y
 
 

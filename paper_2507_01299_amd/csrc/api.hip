@@ -4,9 +4,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "kernels.hpp"
 
 using namespace larosa;
+
+// Scratch of the entry point that allocates nothing (larosa_sparse_gemv_static): arrival counters followed by
+// partial strips, laid out like a caller's workspace.  One copy per GPU the library runs on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[LAROSA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -829,6 +836,54 @@ int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype
                                  static_cast<hipStream_t>(stream)) == hipSuccess
              ? LAROSA_OK
              : LAROSA_EHIP;
+}
+
+// ---- the entry point that allocates nothing ----------------------------------------------------
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once per device
+
+// Device address of this GPU's copy of the scratch array (the current device's), or nullptr.
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    scratch_ptr[dev] = p;
+  }
+  return scratch_ptr[dev];
+}
+
+}  // namespace
+
+int larosa_sparse_gemv_static(const void* Wp, const void* h, const int32_t* idx, void* y, int B, int d_in,
+                              int d_out, int K, larosa_dtype t, void* stream) {
+  if (!Wp || !h || !idx || !y || !dtype_ok(t)) return LAROSA_EINVAL;
+  if (int rc = check_gemv_shapes(B, d_in, d_out, K)) return rc;
+  // the same scratch need as larosa_sparse_gemv's workspace, against the fixed size of the array
+  size_t need;
+  if (B > 1) {
+    const GemvPlan p = plan_batched(d_in, d_out, batched_uses_mfma(B, false));
+    need = round_up(kCounterBytes + batched_partial_bytes(p, B, false), 256) + static_cast<size_t>(B) * d_in * 2;
+  } else {
+    need = kCounterBytes + plan_gemv(d_out, K).partial_floats * sizeof(float);
+  }
+  if (need > LAROSA_STATIC_SCRATCH_BYTES) return LAROSA_EUNSUPPORTED;
+  void* ws = static_scratch();
+  if (!ws) return LAROSA_EHIP;
+  // every call on a GPU shares the array: the counters must start at zero whatever the last call left
+  if (launch_fill_u32(static_cast<unsigned*>(ws), kCounterWords, 0u, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LAROSA_EHIP;
+  const int rc = larosa_sparse_gemv(Wp, h, idx, y, B, d_in, d_out, K, t, ws, LAROSA_STATIC_SCRATCH_BYTES, stream);
+  return rc == LAROSA_EWORKSPACE ? LAROSA_EUNSUPPORTED : rc;
 }
 
 int larosa_set_tuning(int key, int value) {
