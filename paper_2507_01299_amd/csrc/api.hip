@@ -106,6 +106,7 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
   const size_t need = kCounterBytes + static_cast<size_t>(a.B) * p.partial_floats * sizeof(float);
   if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
   a.chunk = p.chunk;
+  a.wps = p.wps;
   a.G = p.G;
   a.nstrips = p.nstrips;
   a.counters = static_cast<unsigned*>(ws);
@@ -144,6 +145,7 @@ int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st)
   if (side) {
     const GemvPlan ps = plan_gemv(a.side.d_out, a.side.K, split.side_g);
     a.side.chunk = ps.chunk;
+    a.side.wps = ps.wps;
     a.side.G = ps.G;
     a.side.nstrips = ps.nstrips;
     a.side.counters = counters + slots * kCounterStride;
@@ -155,6 +157,7 @@ int run_fused(FusedArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st)
   if (slots > kCounterSlots) return LAROSA_EUNSUPPORTED;
   if (!ws || !aligned(ws, 256) || ws_bytes < kCounterBytes + pfloats * sizeof(float)) return LAROSA_EWORKSPACE;
   a.g.chunk = p.chunk;
+  a.g.wps = p.wps;
   a.g.G = p.G;
   a.g.nstrips = p.nstrips;
   a.g.counters = counters;
@@ -820,7 +823,7 @@ int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, con
   if (static_cast<size_t>(B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
   const size_t need = kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float);
   if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
-  a.chunk = p.chunk; a.G = p.G; a.nstrips = p.nstrips;
+  a.chunk = p.chunk; a.wps = p.wps; a.G = p.G; a.nstrips = p.nstrips;
   a.counters = static_cast<unsigned*>(ws);
   a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
   return launch_gemv_w4(w, t == LAROSA_BF16, static_cast<hipStream_t>(stream)) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;

@@ -20,8 +20,180 @@ namespace larosa {
 
 namespace {
 
+// This launch's share of the words it has to clear for a later launch (workgroup g of a.g.G).
+template <int NT>
+__device__ __forceinline__ void clear_words(const FusedArgs& a, int g) {
+  if (a.zero_ptr) {
+    for (int i = g * NT + static_cast<int>(threadIdx.x); i < a.zero_words; i += a.g.G * NT) a.zero_ptr[i] = 0u;
+  }
+}
+
+// The block's input vector, four elements at a time: element group i / 4 of token b.
+__device__ __forceinline__ uint2 load_source4(const FusedArgs& a, int b, int i) {
+  if (a.src_mode == kSrcGqa) {
+    // context-length-1 attention: query head i/head_dim outputs the value head of its group
+    const int head = i / a.head_dim;
+    const int src = (head / a.group) * a.head_dim + (i - head * a.head_dim);
+    return *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * (a.d_q + 2 * a.d_kv) + a.d_q + a.d_kv + src);
+  }
+  return *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * a.g.d_in + i);
+}
+
+// Projection whose input vector arrives with its key histograms (FusedArgs::hist_in): the threshold
+// comes from two small reads by wave 0, every workgroup then only classifies the vector's elements
+// against it, ranks them with one block prefix sum and keeps its own ranks' (row, coefficient) pairs.
+// The vector sits in LDS, transposed ([group of 4][lane], so lane t's elements [tE, (t+1)E) are read
+// without bank conflicts), not in registers: one instantiation serves every width up to kHintMaxWidth.
+struct HintShared {
+  uint2 vec[kHintMaxWidth / 4];   // group q4 of lane t at [q4 * NT + t]
+  unsigned wave_gt[16], wave_eq[16];
+  unsigned T, r;
+};
+
+template <typename T, int RW>
+__global__ __launch_bounds__(RW * 64) void fused_hinted_gemv_kernel(FusedArgs a) {
+  constexpr int NT = RW * 64;
+  __shared__ HintShared hs;
+  __shared__ GemvShared<RW> sh;
+  __shared__ int lst_idx[kFusedChunkMax];
+  __shared__ float lst_val[kFusedChunkMax];
+
+  LAROSA_STAMP(0);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int b = blockIdx.y;
+  const int g = blockIdx.x;
+  clear_words<NT>(a, g);
+  const int d_in = a.g.d_in;
+  const int K = a.g.K;
+  const int E4 = (d_in + NT * 4 - 1) / (NT * 4);   // groups of 4 elements per lane (<= 16)
+  const int base = tid * E4 * 4;
+
+  // ---- the vector into LDS; meanwhile wave 0 reads the threshold off the histograms
+  for (int q4 = 0; q4 < E4; ++q4) {
+    const int i = base + q4 * 4;
+    hs.vec[q4 * NT + tid] = i < d_in ? load_source4(a, b, i) : make_uint2(0u, 0u);
+  }
+  if (rw == 0) {
+    unsigned Tk, r;
+    threshold_from_histograms(a.hist_in + static_cast<size_t>(b) * kHistWords, K, lane, Tk, r);
+    if (lane == 0) {
+      hs.T = Tk;
+      hs.r = r;
+    }
+  }
+  if (a.h_out && g == 0) {
+    for (int q4 = 0; q4 < E4; ++q4) {
+      const int i = base + q4 * 4;
+      if (i < d_in) *reinterpret_cast<uint2*>(a.h_out + static_cast<size_t>(b) * d_in + i) = hs.vec[q4 * NT + tid];
+    }
+  }
+  __syncthreads();
+  LAROSA_STAMP(1);
+  const unsigned Tk = hs.T, r = hs.r;
+
+  // ---- classify this lane's elements, rank them by a block prefix sum
+  unsigned long long m_gt = 0, m_eq = 0;
+  for (int q4 = 0; q4 < E4; ++q4) {
+    const uint2 v = hs.vec[q4 * NT + tid];
+    const unsigned k0 = v.x & 0x7FFFu, k1 = (v.x >> 16) & 0x7FFFu, k2 = v.y & 0x7FFFu, k3 = (v.y >> 16) & 0x7FFFu;
+    const unsigned gt = (k0 > Tk ? 1u : 0u) | (k1 > Tk ? 2u : 0u) | (k2 > Tk ? 4u : 0u) | (k3 > Tk ? 8u : 0u);
+    const unsigned eq = (k0 == Tk ? 1u : 0u) | (k1 == Tk ? 2u : 0u) | (k2 == Tk ? 4u : 0u) | (k3 == Tk ? 8u : 0u);
+    m_gt |= static_cast<unsigned long long>(gt) << (4 * q4);
+    m_eq |= static_cast<unsigned long long>(eq) << (4 * q4);
+  }
+  // padding (zeros past the end of the vector) can only meet T == 0, as ties at the highest indices: never kept
+  TopkLaneT<unsigned long long> st;
+  st.T = Tk;
+  st.r = r;
+  st.m_gt = m_gt;
+  st.m_eq = m_eq;
+  st.n_gt = popc_mask(m_gt);
+  st.n_eq = popc_mask(m_eq);
+  {
+    const unsigned packed = st.n_gt | (st.n_eq << 16);      // a wave holds at most 64 * 64 elements
+    const unsigned incl = wave_scan_inclusive(packed, lane);
+    if (lane == 63) {
+      hs.wave_gt[rw] = incl & 0xFFFFu;
+      hs.wave_eq[rw] = incl >> 16;
+    }
+    __syncthreads();
+    unsigned gt_before = (incl - packed) & 0xFFFFu, eq_before = (incl - packed) >> 16;
+#pragma unroll
+    for (int w = 0; w < RW; ++w) {
+      const unsigned wg = hs.wave_gt[w], we = hs.wave_eq[w];
+      gt_before += (w < rw) ? wg : 0u;
+      eq_before += (w < rw) ? we : 0u;
+    }
+    st.gt_before = gt_before;
+    st.eq_before = eq_before;
+  }
+  LAROSA_STAMP(2);
+
+  // ---- this workgroup's ranks: (row, coefficient) pairs into LDS; workgroup 0 also writes the index list
+  const Segment sg = segment_of(g, a.g.wps, a.g.chunk, K);
+  const int n = sg.t1 - sg.t0;
+  int32_t* idx_out = (a.idx_out && g == 0) ? a.idx_out + static_cast<size_t>(b) * K : nullptr;
+  const int p0 = static_cast<int>(st.first_rank()), p1 = static_cast<int>(st.end_rank());
+  if (idx_out || (p0 < sg.t1 && p1 > sg.t0)) {
+    // threshold ties of this lane that are kept: its first (r - eq_before) ones
+    unsigned long long eq_keep = m_eq;
+    const int want = static_cast<int>(r) - static_cast<int>(st.eq_before);
+    if (want < static_cast<int>(st.n_eq)) {
+      unsigned long long m = m_eq;
+      eq_keep = 0;
+      for (int i = 0; i < want; ++i) {
+        const unsigned long long low = m & (0ull - m);
+        eq_keep |= low;
+        m ^= low;
+      }
+    }
+    const unsigned long long kept = m_gt | eq_keep;
+    unsigned long long left = kept;
+    int pos = p0;
+    while (left) {                         // kept elements of the lane in index order
+      const int q = __builtin_ctzll(left);
+      left &= left - 1;
+      const uint2 v = hs.vec[(q >> 2) * NT + tid];
+      const unsigned w = (q & 2) ? v.y : v.x;
+      const uint16_t bits = static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu));
+      if (idx_out) idx_out[pos] = base + q;
+      const int e = pos - sg.t0;
+      if (static_cast<unsigned>(e) < static_cast<unsigned>(n)) {
+        lst_idx[e] = base + q;
+        lst_val[e] = T::to_f32(bits);
+      }
+      ++pos;
+    }
+  }
+  LAROSA_STAMP(3);
+  __syncthreads();
+  LAROSA_STAMP(4);
+
+  // ---- stream the kept rows of this workgroup's ranks
+  const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out, a.pair_cols, a.pair_out,
+                    a.hist_out, a.hist_col0, a.hist_col1, a.hist_weight};
+  LdsRows rows;
+  rows.idx = lst_idx;
+  rows.val = lst_val;
+  rows.base = sg.t0;
+  bool col_valid;
+  const int col = strip_lane_col(sg.s, lane, a.g.d_out, a.pair_cols, col_valid);
+  float acc[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+  int ra, re;
+  wave_run<RW>(sg.t0, sg.t1, rw, ra, re);
+  stream_rows<T>(a.g.W + col, a.g.d_out, rows, ra, re, acc, col_valid);
+  LAROSA_STAMP(5);
+  reduce_and_finish<T, RW>(acc, sg.s, b, g, a.g.G, a.g.wps, a.g.partial, a.g.counters, a.g.nstrips, ep, sh, lane, rw);
+  LAROSA_STAMP(6);
+}
+
 template <typename T, int RW, int NV>   // RW row-waves; NV 8-byte groups (4 elements each) per lane
-__global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
+// at most 128 vector registers per lane: two 8-wave workgroups (or one of 16 waves) stay resident per compute unit
+__global__ __launch_bounds__(RW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void fused_topk_gemv_kernel(FusedArgs a) {
   constexpr int E = NV * 4;
   constexpr int kFusedRW = RW;
   __shared__ TopkShared<RW> tk;
@@ -29,6 +201,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   __shared__ int lst_idx[kFusedChunkMax];
   __shared__ float lst_val[kFusedChunkMax];
 
+  LAROSA_STAMP(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int rw = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -42,6 +215,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
     }
     g -= a.side_G;
   }
+  clear_words<RW * 64>(a, g);
   const int d_in = a.g.d_in;
   const int K = a.g.K;
   const int base = tid * E;
@@ -53,17 +227,7 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
 #pragma unroll
   for (int q = 0; q < NV; ++q) {
     const int i = base + q * 4;
-    uint2 v = make_uint2(0u, 0u);
-    if (i < d_in) {
-      if (a.src_mode == kSrcGqa) {
-        // context-length-1 attention: query head i/head_dim outputs the value head of its group
-        const int head = i / a.head_dim;
-        const int src = (head / a.group) * a.head_dim + (i - head * a.head_dim);
-        v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * (a.d_q + 2 * a.d_kv) + a.d_q + a.d_kv + src);
-      } else {
-        v = *reinterpret_cast<const uint2*>(a.src + static_cast<size_t>(b) * d_in + i);
-      }
-    }
+    const uint2 v = i < d_in ? load_source4(a, b, i) : make_uint2(0u, 0u);
     raw[q * 4 + 0] = static_cast<uint16_t>(v.x & 0xFFFFu); raw[q * 4 + 1] = static_cast<uint16_t>(v.x >> 16);
     raw[q * 4 + 2] = static_cast<uint16_t>(v.y & 0xFFFFu); raw[q * 4 + 3] = static_cast<uint16_t>(v.y >> 16);
   }
@@ -112,60 +276,48 @@ __global__ __launch_bounds__(RW * 64) void fused_topk_gemv_kernel(FusedArgs a) {
   }
 
   // ---- Top-K select; keep the (row, coefficient) pairs of this workgroup's ranks in LDS
-  const TopkLane st = block_select<kFusedRW, E>(raw, nvalid, K, tk);
-  const int f0 = g * a.g.chunk;
-  const int f1 = min(f0 + a.g.chunk, a.g.nstrips * K);
-  const int sA = f0 / K;
-  const int tA0 = f0 - sA * K;
-  const int nA = min(K - tA0, f1 - f0);   // ranks [tA0, tA0+nA) of strip sA
-  const int nB = (f1 - f0) - nA;          // ranks [0, nB) of strip sA+1; nB <= tA0, so the two never overlap
+  LAROSA_STAMP(1);
+  const auto st = block_select<kFusedRW, E>(raw, K, tk);
+  LAROSA_STAMP(2);
+  const Segment sg = segment_of(g, a.g.wps, a.g.chunk, K);
+  const int n = sg.t1 - sg.t0;            // <= the list capacity by the plan
   int32_t* idx_out = (a.idx_out && g == 0) ? a.idx_out + static_cast<size_t>(b) * K : nullptr;
-  // only lanes whose ranks meet this workgroup's two rank ranges (a few percent) walk their elements
+  // only lanes whose ranks meet this workgroup's rank range (a few percent) walk their elements
   const int p0 = static_cast<int>(st.first_rank()), p1 = static_cast<int>(st.end_rank());
-  if (idx_out || (p0 < tA0 + nA && p1 > tA0) || p0 < nB) {
-    for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned upos, bool kept) {
+  if (idx_out || (p0 < sg.t1 && p1 > sg.t0)) {
+    for_each_kept<E>(st, [&](int q, unsigned upos, bool kept) {
       const int pos = static_cast<int>(upos);
       if (idx_out && kept) idx_out[pos] = base + q;          // idx_out is uniform over the workgroup
-      // entry of the rank in this workgroup's list: segment A holds ranks [tA0, tA0 + nA), segment B
-      // ranks [0, nB); e < nA + nB <= the list capacity by construction
-      const int eA = pos - tA0;
-      const bool inA = static_cast<unsigned>(eA) < static_cast<unsigned>(nA);
-      const bool inB = pos < nB;
-      const int e = inA ? eA : nA + pos;
-      if (kept && (inA || inB)) {
+      const int e = pos - sg.t0;
+      if (kept && static_cast<unsigned>(e) < static_cast<unsigned>(n)) {
         lst_idx[e] = base + q;
         lst_val[e] = T::to_f32(raw[q]);
       }
     });
   }
+  LAROSA_STAMP(3);
   __syncthreads();
+  LAROSA_STAMP(4);
 
-  // ---- stream the kept rows of the (at most two) segments
-  const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out, a.pair_cols, a.pair_out};
-#pragma unroll 1
-  for (int seg_no = 0; seg_no < 2; ++seg_no) {
-    const int n = seg_no == 0 ? nA : nB;
-    if (n <= 0) break;                    // uniform over the workgroup
-    Segment sg;
-    sg.s = sA + seg_no;
-    sg.t0 = seg_no == 0 ? tA0 : 0;
-    sg.t1 = sg.t0 + n;
-    LdsRows rows;
-    rows.idx = lst_idx + (seg_no == 0 ? 0 : nA);
-    rows.val = lst_val + (seg_no == 0 ? 0 : nA);
-    rows.base = sg.t0;
-    bool col_valid;
-    const int col = strip_lane_col(sg.s, lane, a.g.d_out, a.pair_cols, col_valid);
-    float acc[8];
+  // ---- stream the kept rows of this workgroup's ranks
+  const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out, a.pair_cols, a.pair_out,
+                    a.hist_out, a.hist_col0, a.hist_col1, a.hist_weight};
+  LdsRows rows;
+  rows.idx = lst_idx;
+  rows.val = lst_val;
+  rows.base = sg.t0;
+  bool col_valid;
+  const int col = strip_lane_col(sg.s, lane, a.g.d_out, a.pair_cols, col_valid);
+  float acc[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-    const int per = (n + kFusedRW - 1) / kFusedRW;
-    const int ra = sg.t0 + rw * per;
-    const int re = min(sg.t1, ra + per);
-    if (col_valid) stream_rows<T>(a.g.W + col, a.g.d_out, rows, ra, re, acc);
-    reduce_and_finish<T, kFusedRW>(acc, sg, seg_no, b, g, a.g.G, K, a.g.chunk, a.g.nstrips, a.g.partial,
-                                   a.g.counters, ep, sh, lane, rw);
-  }
+  for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+  int ra, re;
+  wave_run<kFusedRW>(sg.t0, sg.t1, rw, ra, re);
+  stream_rows<T>(a.g.W + col, a.g.d_out, rows, ra, re, acc, col_valid);
+  LAROSA_STAMP(5);
+  reduce_and_finish<T, kFusedRW>(acc, sg.s, b, g, a.g.G, a.g.wps, a.g.partial, a.g.counters, a.g.nstrips, ep, sh, lane,
+                                 rw);
+  LAROSA_STAMP(6);
 }
 
 template <typename T, int RW>
@@ -189,7 +341,16 @@ hipError_t launch_nv(const FusedArgs& a, hipStream_t st) {
 }
 
 template <typename T>
+hipError_t launch_hinted(const FusedArgs& a, hipStream_t st) {
+  if (a.side_G > 0 || a.src_mode == kSrcNorm || a.g.d_in > kHintMaxWidth) return hipErrorInvalidValue;
+  dim3 grid(a.g.G, a.g.B), block(8 * 64);
+  hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 8>), grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+template <typename T>
 hipError_t launch_rw(const FusedArgs& a, hipStream_t st) {
+  if (a.hist_in) return launch_hinted<T>(a, st);
   return fused_row_waves() == 16 ? launch_nv<T, 16>(a, st) : launch_nv<T, 8>(a, st);
 }
 
@@ -199,22 +360,10 @@ int fused_row_waves() { return tuning().fused_rw == 16 ? 16 : 8; }
 
 GemvPlan plan_fused(int d_out, int K, int g_hint, int pair_cols) {
   // paired strips: ceil(d_ff / 256) strips of 512 columns (256 gate + 256 up); plan_gemv only needs the count
-  GemvPlan p = plan_gemv(pair_cols > 0 ? (pair_cols + 255) / 256 * kStripCols : d_out, K, g_hint);
-  if (fused_row_waves() == 16 && tuning().g_target == 0 && g_hint == 0 && p.G > 256) {
-    // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
-    const long T = static_cast<long>(p.nstrips) * K;
-    long G = 256 > p.nstrips ? 256 : p.nstrips;
-    p.chunk = static_cast<int>((T + G - 1) / G);
-    p.G = static_cast<int>((T + p.chunk - 1) / p.chunk);
-    p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;
-  }
-  if (p.chunk > kFusedChunkMax) {       // the workgroup's rank list must fit its LDS arrays
-    const long T = static_cast<long>(p.nstrips) * K;
-    p.chunk = kFusedChunkMax;
-    p.G = static_cast<int>((T + p.chunk - 1) / p.chunk);
-    p.partial_floats = static_cast<size_t>(p.G) * 2 * kStripCols;
-  }
-  return p;
+  const int cols = pair_cols > 0 ? (pair_cols + 255) / 256 * kStripCols : d_out;
+  if (fused_row_waves() == 16 && tuning().g_target == 0 && g_hint == 0)
+    g_hint = 256;   // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
+  return plan_gemv(cols, K, g_hint, kStripCols, kFusedChunkMax);
 }
 
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s) {

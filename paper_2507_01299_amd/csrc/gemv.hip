@@ -3,10 +3,10 @@
 // adapter / baseline.
 //
 // The weight is input-channel-major, so a kept input channel is one contiguous run of d_out
-// 16-bit values.  Work is the set of (column strip, kept row) pairs, cut into equal contiguous
-// chunks over all workgroups so every workgroup moves the same number of bytes whatever the
-// shape; a workgroup therefore touches at most two strips ("segments").  The shared pieces
-// (row loop, reductions, epilogue) are in gemv_core.hpp.
+// 16-bit values.  Work is the set of (column strip, kept row) pairs; every strip's kept rows are cut
+// into equal runs over the same number of workgroups, so every workgroup moves the same number of
+// bytes and hands over exactly one partial strip.  The shared pieces (row loop, reductions, epilogue)
+// are in gemv_core.hpp.
 #include "gemv_core.hpp"
 
 namespace larosa {
@@ -47,18 +47,26 @@ Tuning& tuning() {
   return t;
 }
 
-GemvPlan plan_gemv(int d_out, int K, int g_hint, int strip_cols) {
+GemvPlan plan_gemv(int d_out, int K, int g_hint, int strip_cols, int max_ranks) {
   GemvPlan p;
   p.strip_cols = strip_cols;
   p.nstrips = (d_out + strip_cols - 1) / strip_cols;
   const long T = static_cast<long>(p.nstrips) * K;
-  // 256 compute units: one workgroup each for small problems, two each otherwise
-  long G = g_hint > 0 ? g_hint : tuning().g_target > 0 ? tuning().g_target : (T < 32768 ? 256 : 512);
-  if (G > T / tuning().min_rows) G = T / tuning().min_rows;
-  if (G < p.nstrips) G = p.nstrips;
-  p.chunk = static_cast<int>((T + G - 1) / G);
-  p.G = static_cast<int>((T + p.chunk - 1) / p.chunk);
-  p.partial_floats = static_cast<size_t>(p.G) * 2 * strip_cols;
+  // 256 compute units, one workgroup each (a second one per unit does not raise the row-streaming rate
+  // and doubles the per-unit cost of everything the workgroups do redundantly); every workgroup works
+  // on one strip, so the count is a multiple of the number of strips (rounded down: what is left idle
+  // is a few compute units, not bandwidth)
+  long G = g_hint > 0 ? g_hint : tuning().g_target > 0 ? tuning().g_target : 256;
+  (void)T;
+  long wps = G / p.nstrips;
+  if (wps > K / tuning().min_rows) wps = K / tuning().min_rows;
+  if (wps < 1) wps = 1;
+  long per = (K + wps - 1) / wps;
+  if (max_ranks > 0 && per > max_ranks) per = max_ranks;   // the workgroup's rank list must fit its LDS arrays
+  p.chunk = static_cast<int>(per);
+  p.wps = static_cast<int>((K + per - 1) / per);           // every workgroup of a strip has ranks
+  p.G = p.nstrips * p.wps;
+  p.partial_floats = static_cast<size_t>(p.G) * strip_cols;
   return p;
 }
 

@@ -15,10 +15,10 @@ struct GemvArgs {
   const int32_t* idx;         // [B, K] or nullptr (dense: K == d_in)
   uint16_t* y;                // [B, d_out]
   int d_in, d_out, K, B;
-  // work split: row-strips (strip s, kept row t) are numbered f = s*K + t; workgroup g takes
-  // [g*chunk, (g+1)*chunk).  chunk <= K, so a workgroup touches at most two strips.
-  int chunk, G, nstrips;
-  float* partial;             // [B][G][2][strip_cols] fp32 partial sums
+  // work split: workgroup g takes strip g / wps and, with j = g mod wps, the ranks
+  // [j*chunk, min(K, (j+1)*chunk)) of the kept list: one strip per workgroup, G = nstrips * wps.
+  int chunk, G, nstrips, wps;
+  float* partial;             // [B][G][strip_cols] fp32 partial sums
   unsigned* counters;         // [B][nstrips] arrival counters (kCounterStride apart), zero on entry and on exit
   // epilogue
   const uint16_t* coef_scale; // [d_in] or nullptr: multiplies the coefficient (pre-norm scale)
@@ -32,6 +32,7 @@ constexpr int kCounterStride = 64;   // in 32-bit words: one arrival counter per
 
 struct GemvPlan {
   int strip_cols, nstrips, chunk, G;
+  int wps;                    // workgroups per strip (row-streaming kernels; the batched kernels split differently)
   size_t partial_floats;      // per token
 };
 
@@ -49,7 +50,8 @@ struct Tuning {
 Tuning& tuning();
 
 // g_hint > 0 asks for that many workgroups instead of the automatic choice
-GemvPlan plan_gemv(int d_out, int K, int g_hint = 0, int strip_cols = 512);
+// max_ranks > 0 caps the ranks per workgroup (more workgroups per strip instead)
+GemvPlan plan_gemv(int d_out, int K, int g_hint = 0, int strip_cols = 512, int max_ranks = 0);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
 
 // The same mat-vec over 4-bit weights (w4.hip): g.W is unused; the row loop reads packed codes and
@@ -92,7 +94,16 @@ struct FusedArgs {
   // workgroups also store pair_out [B, d_ff] = R(SiLU(gate) * up).  The plan must use d_ff / 256 strips.
   int pair_cols;
   uint16_t* pair_out;
+  // Histograms handed from the producer of a vector to the launch that selects on it (kHistWords words
+  // per token, zero before the producer runs; see topk_core.hpp):
+  const unsigned* hist_in;    // nullable: histograms of the keys of this launch's input vector, complete
+  unsigned* hist_out;         // nullable: the finishing workgroups add the keys of pair_out (paired strips) or
+  int hist_col0, hist_col1;   //   of the y columns [hist_col0, hist_col1), each counting hist_weight times
+  unsigned hist_weight;
+  unsigned* zero_ptr;         // nullable: zero_words words that this launch clears (histograms a later launch fills)
+  int zero_words;
 };
+constexpr int kHintMaxWidth = 32768;   // widest input vector of the launch form that takes hist_in
 // pair_cols > 0: strips are 256 channels of gate and of up each (see FusedArgs)
 GemvPlan plan_fused(int d_out, int K, int g_hint = 0, int pair_cols = 0);
 int fused_row_waves();

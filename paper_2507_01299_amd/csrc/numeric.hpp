@@ -3,6 +3,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Phase clocks of a diagnostic build (-DLAROSA_PHASE_CLOCK): lane 0 of a workgroup stores the
+// 100 MHz wall clock to slot `n` of its row in a buffer whose address the host puts into
+// larosa_phase_clock (null: off).  Product builds compile the stamps to nothing.
+#ifdef LAROSA_PHASE_CLOCK
+static __device__ unsigned long long* larosa_phase_clock = nullptr;
+constexpr int kPhaseSlots = 16;
+#define LAROSA_STAMP(n)                                                                         \
+  do {                                                                                          \
+    if (threadIdx.x == 0 && larosa_phase_clock)                                                 \
+      larosa_phase_clock[(blockIdx.y * gridDim.x + blockIdx.x) * kPhaseSlots + (n)] = wall_clock64(); \
+  } while (0)
+#else
+#define LAROSA_STAMP(n) do { } while (0)
+#endif
+
 namespace larosa {
 
 constexpr int kWave = 64;

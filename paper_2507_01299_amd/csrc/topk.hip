@@ -122,14 +122,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
     }
   }
   if (sc.mode != kSrcNorm) __syncthreads();
-  const TopkLane st = block_select<kTopkWaves, E>(raw, nvalid, K, sm);
+  const auto st = block_select<kTopkWaves, E>(raw, K, sm);
 
   int32_t* idxb = idx + static_cast<size_t>(b) * K;
   uint16_t* valb = vals ? vals + static_cast<size_t>(b) * K : nullptr;
   uint16_t mk[E];
 #pragma unroll
   for (int q = 0; q < E; ++q) mk[q] = 0;
-  for_each_kept<E>(raw, nvalid, st, [&](int q, unsigned pos, bool kept) {
+  for_each_kept<E>(st, [&](int q, unsigned pos, bool kept) {
     if (kept) {
       idxb[pos] = base + q;
       if (valb) valb[pos] = raw[q];

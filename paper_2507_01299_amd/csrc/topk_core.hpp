@@ -8,13 +8,18 @@
 //      bfloat16 the 8 bits are the exponent alone), and lanes of one wave that add to the same LDS
 //      word are served one per clock; so there are kTopkCopies histograms (in different banks for one
 //      bin) and a lane adds to copy (lane mod kTopkCopies): at most 64 / kTopkCopies lanes meet in a
-//      word whatever the data.
-//      Suffix sums from the top locate the bin holding the K-th largest key;
-//   2. 128-bin histogram (same copies) of the low 7 bits inside that bin gives the threshold key T and
-//      r = K - #{key > T}, the number of threshold ties to keep;
-//   3. block prefix sums of the ">T" and "==T" counts give every lane the number of kept
+//      word whatever the data.  After ONE barrier every wave sums the copies and walks the bins from
+//      the top by itself (suffix sums on the data-parallel path), so the bin holding the K-th largest
+//      key needs no broadcast through LDS and no second barrier;
+//   2. 128-bin histogram of the low 7 bits inside that bin, one copy PER WAVE.  After one more barrier
+//      every wave reads all copies: their sum gives the threshold key T and r = K - #{key > T}, the
+//      number of threshold ties to keep, and the copies of the waves before it give the number of
+//      kept elements of that bin in front of the wave -- the block prefix needs no barrier of its own.
+//      (The counts of elements in higher bins travel as one total per wave with the same barrier.)
+//   3. a wave-level prefix sum of the ">T" and "==T" counts then gives every lane the number of kept
 //      elements before its own, so an index-ordered compaction keeps every key > T and the first
 //      r keys == T: ascending indices and the lower-index tie rule with no sort.
+// Two barriers in all (after the one that makes the cleared histograms and the vector visible).
 #pragma once
 #include <cstddef>
 
@@ -23,26 +28,45 @@
 namespace larosa {
 
 constexpr int kTopkCopies = 8;
+// Pass 1's 256 bins times kTopkCopies are 8 KiB to read: one wave walks them and hands the bin on through
+// LDS (one more barrier); every wave doing it by itself measured slower with two workgroups per compute unit.
+#ifndef LAROSA_TOPK_ALL_WAVES_SCAN1
+#define LAROSA_TOPK_ALL_WAVES_SCAN1 0
+#endif
+constexpr bool kTopkAllWavesScan1 = LAROSA_TOPK_ALL_WAVES_SCAN1 != 0;
 constexpr int kTopkCopyStride = 260;   // words between copies: 16-byte aligned, and the copies of one bin fall in different LDS banks
-constexpr int kTopkCopyStride2 = 132;  // the same for the 128-bin pass
+constexpr int kTopkCopyStride2 = 132;  // the same for the 128-bin pass (one copy per wave)
 
 template <int NW>
 struct TopkShared {
   alignas(16) unsigned hist[kTopkCopyStride * kTopkCopies];   // pass 1: word copy * kTopkCopyStride + bin
-  unsigned hist2[kTopkCopyStride2 * kTopkCopies];            // pass 2 (adjacent, so both are cleared in one step)
-  unsigned wave_tot[NW];
-  int bin, bin2;            // pass-1 / pass-2 bin holding the K-th largest key
-  unsigned above, above2;   // counts strictly above those bins
+  unsigned hist2[kTopkCopyStride2 * NW];                      // pass 2: word wave * kTopkCopyStride2 + bin (adjacent: cleared in one step)
+  unsigned wave_tot[NW];                                      // per wave: elements in bins above the threshold bin
+  int bin;                                                    // pass-1 bin holding the K-th largest key, and the
+  unsigned above;                                             // count strictly above it (written by wave 0)
 };
 
+// one bit per element of a lane
+template <int E> struct LaneMask { typedef unsigned long long type; };
+template <> struct LaneMask<4> { typedef unsigned type; };
+template <> struct LaneMask<8> { typedef unsigned type; };
+template <> struct LaneMask<12> { typedef unsigned type; };
+template <> struct LaneMask<16> { typedef unsigned type; };
+template <> struct LaneMask<24> { typedef unsigned type; };
+template <> struct LaneMask<32> { typedef unsigned type; };
+
+__device__ __forceinline__ unsigned popc_mask(unsigned m) { return static_cast<unsigned>(__popc(m)); }
+__device__ __forceinline__ unsigned popc_mask(unsigned long long m) { return static_cast<unsigned>(__popcll(m)); }
+
 // Selection state of one lane after block_select.
-struct TopkLane {
+template <typename Mask>
+struct TopkLaneT {
   unsigned T;          // threshold key
   unsigned r;          // number of keys == T to keep (>= 1)
   unsigned gt_before;  // kept-by-magnitude elements before this lane's first element
   unsigned eq_before;  // threshold ties before this lane's first element
   unsigned n_gt, n_eq; // this lane's own counts of keys > T and == T
-  unsigned long long m_gt, m_eq;   // bit q set: this lane's element q has key > T / == T
+  Mask m_gt, m_eq;     // bit q set: this lane's element q has key > T / == T
   // ranks [first, end) of the ascending kept list held by this lane
   __device__ __forceinline__ unsigned first_rank() const { return gt_before + min(eq_before, r); }
   __device__ __forceinline__ unsigned end_rank() const { return gt_before + n_gt + min(eq_before + n_eq, r); }
@@ -52,7 +76,7 @@ struct TopkLane {
 // (it usually has one of its own while it builds the vector) makes the zeros visible.
 template <int NW>
 __device__ __forceinline__ void topk_clear(TopkShared<NW>& sm) {
-  constexpr int kWords = (kTopkCopyStride + kTopkCopyStride2) * kTopkCopies;   // hist and hist2 are adjacent
+  constexpr int kWords = kTopkCopyStride * kTopkCopies + kTopkCopyStride2 * NW;   // hist and hist2 are adjacent
   static_assert(offsetof(TopkShared<NW>, hist2) == sizeof(unsigned) * kTopkCopyStride * kTopkCopies,
                 "histograms must be adjacent");
   static_assert(offsetof(TopkShared<NW>, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
@@ -60,17 +84,24 @@ __device__ __forceinline__ void topk_clear(TopkShared<NW>& sm) {
   for (int i = threadIdx.x; i < kWords / 4; i += NW * 64) flat[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
-// raw[q] (q < nvalid) are this lane's stored 16-bit values; raw[q] for q >= nvalid (positions past
-// the end of the vector) MUST be zero.  Such padding is counted like a zero at an index above every
-// real element: it is never above the threshold, and among threshold ties the lower-index rule takes
-// the real elements first (K is at most their number), so it is never kept -- and the three passes
-// over the elements need no per-element predicate.  Every lane of the NW-wave workgroup must call
-// this, after topk_clear and a workgroup barrier.  1 <= K <= total number of valid elements <= 32768.
+// Sum over the 64 lanes, the same value in every lane (and known to be uniform).
+__device__ __forceinline__ unsigned wave_total(unsigned v, int lane) {
+  return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(wave_scan_inclusive(v, lane)), 63));
+}
+
+// raw[q] are this lane's stored 16-bit values; positions past the end of the vector MUST hold zero.
+// Such padding is counted like a zero at an index above every real element: it is never above the
+// threshold, and among threshold ties the lower-index rule takes the real elements first (K is at most
+// their number), so it is never kept -- and the passes over the elements need no per-element predicate.
+// Every lane of the NW-wave workgroup must call this, after topk_clear and a workgroup barrier.
+// 1 <= K <= total number of valid elements <= 32768.
 template <int NW, int E>
-__device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int nvalid, int K, TopkShared<NW>& sm) {
+__device__ __forceinline__ TopkLaneT<typename LaneMask<E>::type> block_select(const uint16_t (&raw)[E], int K,
+                                                                              TopkShared<NW>& sm) {
+  typedef typename LaneMask<E>::type Mask;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- pass 1: top 8 key bits
   unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride;
@@ -78,92 +109,204 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
   for (int q = 0; q < E; ++q)
     atomicAdd(&mine[(raw[q] & 0x7FFFu) >> 7], 1u);
   __syncthreads();
-  if (wave == 0) {
+  int bin1;
+  unsigned above1;
+  if (kTopkAllWavesScan1 || wave == 0) {
     // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p; its four
     // counts of one copy are one aligned 16-byte read
-    unsigned c[4] = {0u, 0u, 0u, 0u}, local = 0;
+    unsigned c[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int k = 0; k < kTopkCopies; ++k) {
       const uint4 v = *reinterpret_cast<const uint4*>(sm.hist + k * kTopkCopyStride + 252 - 4 * lane);
       c[0] += v.w; c[1] += v.z; c[2] += v.y; c[3] += v.x;
     }
-    local = (c[0] + c[1]) + (c[2] + c[3]);
+    const unsigned local = (c[0] + c[1]) + (c[2] + c[3]);
     const unsigned need = static_cast<unsigned>(K);
     unsigned run = wave_scan_inclusive(local, lane) - local;
+    int cand = -1;
+    unsigned cand_above = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const unsigned before = run;
       run += c[q];
       if (before < need && run >= need) {
-        sm.bin = 255 - (lane * 4 + q);
-        sm.above = before;
+        cand = 255 - (lane * 4 + q);
+        cand_above = before;
       }
     }
+    // exactly one lane holds the bin (1 <= K <= number of counted elements)
+    if (kTopkAllWavesScan1) {
+      const unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
+      const int src = found ? __builtin_ctzll(found) : 0;
+      bin1 = __builtin_amdgcn_readlane(cand, src);
+      above1 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
+    } else if (cand >= 0) {
+      sm.bin = cand;
+      sm.above = cand_above;
+    }
   }
-  __syncthreads();
-  const int bin1 = sm.bin;
-  const unsigned above1 = sm.above;
+  if (!kTopkAllWavesScan1) {
+    __syncthreads();
+    bin1 = sm.bin;
+    above1 = sm.above;
+  }
 
-  // ---- pass 2: low 7 bits inside bin1
-  unsigned* mine2 = sm.hist2 + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride2;
+  // ---- pass 2: low 7 bits inside bin1 (this wave's copy), and the wave's count of elements in higher bins
+  unsigned* mine2 = sm.hist2 + wave * kTopkCopyStride2;
+  Mask m_hi = 0;
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    if (static_cast<int>(key >> 7) == bin1) atomicAdd(&mine2[key & 127u], 1u);
+    const int cb = static_cast<int>(key >> 7);
+    if (cb == bin1) atomicAdd(&mine2[key & 127u], 1u);
+    m_hi |= static_cast<Mask>(cb > bin1 ? 1u : 0u) << q;
+  }
+  {
+    const unsigned tot_hi = wave_total(popc_mask(m_hi), lane);
+    if (lane == 0) sm.wave_tot[wave] = tot_hi;
   }
   __syncthreads();
-  if (wave == 0) {
-    unsigned c[2] = {0u, 0u};
+  TopkLaneT<Mask> out;
+  unsigned base_gt, base_eq;   // kept-by-magnitude elements / threshold ties in the waves before this one
+  {
+    // lane covers bins 127 - 2*lane (c[0]) and 126 - 2*lane (c[1]): one 8-byte read per wave copy;
+    // p[] = the same two bins summed over the waves before this one
+    unsigned c[2] = {0u, 0u}, p[2] = {0u, 0u};
 #pragma unroll
-    for (int k = 0; k < kTopkCopies; ++k) {   // bins 127 - 2*lane (c[0]) and 126 - 2*lane (c[1]): one 8-byte read per copy
+    for (int k = 0; k < NW; ++k) {
       const uint2 v = *reinterpret_cast<const uint2*>(sm.hist2 + k * kTopkCopyStride2 + 126 - 2 * lane);
       c[0] += v.y; c[1] += v.x;
+      if (k < wave) { p[0] += v.y; p[1] += v.x; }   // uniform condition
     }
     const unsigned local = c[0] + c[1];
     const unsigned need = static_cast<unsigned>(K) - above1;
     unsigned run = wave_scan_inclusive(local, lane) - local;
+    int cand = -1;
+    unsigned cand_above = 0;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const unsigned before = run;
       run += c[q];
       if (before < need && run >= need) {
-        sm.bin2 = 127 - (lane * 2 + q);
-        sm.above2 = before;
+        cand = 127 - (lane * 2 + q);
+        cand_above = before;
       }
     }
+    const unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
+    const int src = found ? __builtin_ctzll(found) : 0;
+    const int bin2 = __builtin_amdgcn_readlane(cand, src);
+    const unsigned above2 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
+    out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(bin2);
+    out.r = static_cast<unsigned>(K) - (above1 + above2);
+    // elements of the threshold bin above / at T in earlier waves, plus earlier waves' higher-bin totals
+    // (lane k < wave adds wave_tot[k]); packed as gt | eq << 16, each at most 32768
+    const int b0 = 127 - 2 * lane, b1 = 126 - 2 * lane;
+    unsigned gt = (b0 > bin2 ? p[0] : 0u) + (b1 > bin2 ? p[1] : 0u);
+    const unsigned eq = (b0 == bin2 ? p[0] : 0u) + (b1 == bin2 ? p[1] : 0u);
+    if (lane < wave) gt += sm.wave_tot[lane];      // wave <= NW <= 16 < 64
+    // the two sums are reduced separately: their packed total could carry (32768 + 32768 in one half)
+    base_gt = wave_total(gt, lane);
+    base_eq = wave_total(eq, lane);
   }
-  __syncthreads();
-  TopkLane out;
-  out.T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(sm.bin2);
-  out.r = static_cast<unsigned>(K) - (above1 + sm.above2);
 
   // per-lane bit masks of the two classes (independent compares: no chain from element to element)
-  unsigned long long m_gt = 0, m_eq = 0;
+  Mask m_gt = 0, m_eq = 0;
 #pragma unroll
   for (int q = 0; q < E; ++q) {
     const unsigned key = raw[q] & 0x7FFFu;
-    m_gt |= static_cast<unsigned long long>(key > out.T ? 1u : 0u) << q;
-    m_eq |= static_cast<unsigned long long>(key == out.T ? 1u : 0u) << q;
+    m_gt |= static_cast<Mask>(key > out.T ? 1u : 0u) << q;
+    m_eq |= static_cast<Mask>(key == out.T ? 1u : 0u) << q;
   }
-  (void)nvalid;
-  const unsigned n_gt = static_cast<unsigned>(__popcll(m_gt)), n_eq = static_cast<unsigned>(__popcll(m_eq));
+  const unsigned n_gt = popc_mask(m_gt), n_eq = popc_mask(m_eq);
   out.m_gt = m_gt;
   out.m_eq = m_eq;
-  const unsigned packed = n_gt | (n_eq << 16);          // each total <= 32768: no carry between halves
-  const unsigned incl = wave_scan_inclusive(packed, lane);
-  if (lane == 63) sm.wave_tot[wave] = incl;
-  __syncthreads();
-  unsigned prefix = incl - packed;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {          // all totals are read at once; a loop to `wave` would chain the reads
-    const unsigned t = sm.wave_tot[w];
-    prefix += (w < wave) ? t : 0u;
-  }
-  out.gt_before = prefix & 0xFFFFu;
-  out.eq_before = prefix >> 16;
+  // within the wave: one wave holds at most 64 * E <= 4096 elements, so both counts fit 16-bit halves
+  const unsigned packed = n_gt | (n_eq << 16);
+  const unsigned excl = wave_scan_inclusive(packed, lane) - packed;
+  out.gt_before = base_gt + (excl & 0xFFFFu);
+  out.eq_before = base_eq + (excl >> 16);
   out.n_gt = n_gt;
   out.n_eq = n_eq;
   return out;
+}
+
+// ---- selection from histograms that the producer of the vector has already built ------------------
+//
+// A vector that one of the library's own kernels writes (the MLP intermediate vector, a rotated block
+// input) can arrive with the two histograms of its keys in device memory: hist[0 .. 256) counts the top
+// 8 key bits, hist[256 + key] every 15-bit key (the workgroups that store the vector's strips add their
+// elements with device atomics).  The threshold then costs two small dependent reads by one wave instead
+// of two histogram passes over the vector in every workgroup.
+constexpr int kHistCoarse = 256;
+constexpr int kHistWords = kHistCoarse + 32768;
+
+// Threshold key T and tie quota r = K - #{key > T} from such histograms; called by all 64 lanes of one
+// wave, result in every lane.  1 <= K <= number of counted elements.
+__device__ __forceinline__ void threshold_from_histograms(const unsigned* __restrict__ hist, int K, int lane,
+                                                          unsigned& T, unsigned& r) {
+  const uint4 v = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // bins 255 - 4 lane - q in .w .z .y .x
+  const unsigned c[4] = {v.w, v.z, v.y, v.x};
+  const unsigned local = (c[0] + c[1]) + (c[2] + c[3]);
+  unsigned need = static_cast<unsigned>(K);
+  unsigned run = wave_scan_inclusive(local, lane) - local;
+  int cand = -1;
+  unsigned cand_above = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const unsigned before = run;
+    run += c[q];
+    if (before < need && run >= need) {
+      cand = 255 - (lane * 4 + q);
+      cand_above = before;
+    }
+  }
+  unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
+  int src = found ? __builtin_ctzll(found) : 0;
+  const int bin1 = max(0, __builtin_amdgcn_readlane(cand, src));
+  const unsigned above1 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
+  const uint2 f = *reinterpret_cast<const uint2*>(hist + kHistCoarse + bin1 * 128 + 126 - 2 * lane);
+  const unsigned c2[2] = {f.y, f.x};                                        // bins 127 - 2 lane, 126 - 2 lane
+  need -= above1;
+  run = wave_scan_inclusive(c2[0] + c2[1], lane) - (c2[0] + c2[1]);
+  cand = -1;
+  cand_above = 0;
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const unsigned before = run;
+    run += c2[q];
+    if (before < need && run >= need) {
+      cand = 127 - (lane * 2 + q);
+      cand_above = before;
+    }
+  }
+  found = __builtin_amdgcn_ballot_w64(cand >= 0);
+  src = found ? __builtin_ctzll(found) : 0;
+  const int bin2 = max(0, __builtin_amdgcn_readlane(cand, src));
+  const unsigned above2 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
+  T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(bin2);
+  r = static_cast<unsigned>(K) - (above1 + above2);
+}
+
+// Producer side: the eight stored 16-bit values of each lane of ONE wave (valid lanes only) are added to
+// the histograms, each counting `weight` times.  The coarse counts are summed in `scratch` (256 words of
+// LDS owned by this wave) first, so a bin that many strips fill costs one device atomic per strip and
+// not one per element.  All 64 lanes must call it.
+__device__ __forceinline__ void histograms_add_wave(const uint16_t (&bits)[8], bool valid, unsigned weight,
+                                                    unsigned* __restrict__ hist, unsigned* scratch, int lane) {
+  reinterpret_cast<uint4*>(scratch)[lane] = make_uint4(0u, 0u, 0u, 0u);
+  if (valid) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const unsigned key = bits[k] & 0x7FFFu;
+      atomicAdd(&scratch[key >> 7], weight);
+      atomicAdd(&hist[kHistCoarse + key], weight);
+    }
+  }
+  const uint4 c = reinterpret_cast<const uint4*>(scratch)[lane];   // same wave: LDS operations complete in order
+  if (c.x) atomicAdd(&hist[4 * lane + 0], c.x);
+  if (c.y) atomicAdd(&hist[4 * lane + 1], c.y);
+  if (c.z) atomicAdd(&hist[4 * lane + 2], c.z);
+  if (c.w) atomicAdd(&hist[4 * lane + 3], c.w);
 }
 
 // Visit this lane's elements in index order; emit(q, pos, kept) is called for EVERY element q < E, with
@@ -171,26 +314,26 @@ __device__ __forceinline__ TopkLane block_select(const uint16_t (&raw)[E], int n
 // fold `kept` into their store predicate: a branch per element costs more than the stores).  Kept = key > T, plus the first r threshold ties in index
 // order; a kept element's rank is the lane's first rank plus the number of kept elements before it
 // in the lane, so every element is handled independently of the others.
-template <int E, typename F>
-__device__ __forceinline__ void for_each_kept(const uint16_t (&raw)[E], int nvalid, const TopkLane& st, F emit) {
-  (void)raw; (void)nvalid;
+template <int E, typename Mask, typename F>
+__device__ __forceinline__ void for_each_kept(const TopkLaneT<Mask>& st, F emit) {
   // threshold ties of this lane that are kept: its first (r - eq_before) ones
-  unsigned long long eq_keep = st.m_eq;
+  Mask eq_keep = st.m_eq;
   const int want = static_cast<int>(st.r) - static_cast<int>(st.eq_before);
   if (want < static_cast<int>(st.n_eq)) {            // rare: the tie quota ends inside this lane
-    unsigned long long m = st.m_eq;
+    Mask m = st.m_eq;
     eq_keep = 0;
     for (int i = 0; i < want; ++i) {
-      const unsigned long long low = m & (0ull - m);
+      const Mask low = m & (static_cast<Mask>(0) - m);
       eq_keep |= low;
       m ^= low;
     }
   }
-  const unsigned long long kept = st.m_gt | eq_keep;
+  const Mask kept = st.m_gt | eq_keep;
   const unsigned first = st.first_rank();
 #pragma unroll
   for (int q = 0; q < E; ++q)
-    emit(q, first + static_cast<unsigned>(__popcll(kept & ((1ull << q) - 1ull))), ((kept >> q) & 1ull) != 0ull);
+    emit(q, first + popc_mask(static_cast<Mask>(kept & ((static_cast<Mask>(1) << q) - static_cast<Mask>(1)))),
+         ((kept >> q) & static_cast<Mask>(1)) != 0);
 }
 
 }  // namespace larosa

@@ -132,42 +132,26 @@ __global__ __launch_bounds__(RW * 64, 2) void gemv_rows_w4_wide_kernel(W4Args w)
   const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out, 0, nullptr};
   const int row_dwords = a.d_out / 8;
 
-  int f0 = g * a.chunk;
-  const int f1 = min(f0 + a.chunk, a.nstrips * K);
-  Segment sg{f0 / K, 0, 0};
-  sg.t0 = f0 - sg.s * K;
-  const bool staged = INDEXED && stage_row_list<RW * 64, kW4WideList>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
-  int seg_no = 0;
-  int list_base = 0;
-  while (f0 < f1) {
-    sg.t1 = min(K, sg.t0 + (f1 - f0));
-    const int col = sg.s * kW4WideCols + lane * kW4WideAcc;
-    float acc[kW4WideAcc];
+  const Segment sg = segment_of(g, a.wps, a.chunk, K);
+  const bool staged = INDEXED && stage_row_list<RW * 64, kW4WideList>(rows, sg.t0, sg.t1 - sg.t0, lst_idx, lst_val);
+  const int col = sg.s * kW4WideCols + lane * kW4WideAcc;
+  float acc[kW4WideAcc];
 #pragma unroll
-    for (int k = 0; k < kW4WideAcc; ++k) acc[k] = 0.f;
-    const int n = sg.t1 - sg.t0;
-    const int per = (n + RW - 1) / RW;
-    const int ra = sg.t0 + rw * per;
-    const int re = min(sg.t1, ra + per);
-    if (col < a.d_out) {
-      if (staged) {
-        LdsRows lr;
-        lr.idx = lst_idx + list_base;
-        lr.val = lst_val + list_base;
-        lr.base = sg.t0;
-        stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
-      } else {
-        stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
-      }
+  for (int k = 0; k < kW4WideAcc; ++k) acc[k] = 0.f;
+  int ra, re;
+  wave_run<RW>(sg.t0, sg.t1, rw, ra, re);
+  if (col < a.d_out) {
+    if (staged) {
+      LdsRows lr;
+      lr.idx = lst_idx;
+      lr.val = lst_val;
+      lr.base = sg.t0;
+      stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
+    } else {
+      stream_rows_w4_wide<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
     }
-    reduce_and_finish<T, RW, kW4WideAcc>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep,
-                                         sh, lane, rw);
-    list_base += n;
-    f0 += sg.t1 - sg.t0;
-    sg.s += 1;
-    sg.t0 = 0;
-    seg_no += 1;
   }
+  reduce_and_finish<T, RW, kW4WideAcc>(acc, sg.s, b, g, a.G, a.wps, a.partial, a.counters, a.nstrips, ep, sh, lane, rw);
 }
 
 template <typename T, int RW, bool INDEXED>
@@ -189,42 +173,26 @@ __global__ __launch_bounds__(RW * 64) void gemv_rows_w4_kernel(W4Args w) {
   const Epilogue ep{a.y, a.rms_src, a.rms_eps, a.residual, a.y_pre, a.d_in, a.d_out, 0, nullptr};
   const int row_dwords = a.d_out / 8;
 
-  int f0 = g * a.chunk;
-  const int f1 = min(f0 + a.chunk, a.nstrips * K);
-  Segment sg{f0 / K, 0, 0};
-  sg.t0 = f0 - sg.s * K;
-  const bool staged = INDEXED && stage_row_list<RW * 64>(rows, sg.t0, f1 - f0, K, lst_idx, lst_val);
-  int seg_no = 0;
-  int list_base = 0;
-  while (f0 < f1) {
-    sg.t1 = min(K, sg.t0 + (f1 - f0));
-    const int col = sg.s * kStripCols + lane * 8;
-    float acc[8];
+  const Segment sg = segment_of(g, a.wps, a.chunk, K);
+  const bool staged = INDEXED && stage_row_list<RW * 64>(rows, sg.t0, sg.t1 - sg.t0, lst_idx, lst_val);
+  const int col = sg.s * kStripCols + lane * 8;
+  float acc[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
-    const int n = sg.t1 - sg.t0;
-    const int per = (n + RW - 1) / RW;
-    const int ra = sg.t0 + rw * per;
-    const int re = min(sg.t1, ra + per);
-    if (col < a.d_out) {
-      if (staged) {
-        LdsRows lr;
-        lr.idx = lst_idx + list_base;
-        lr.val = lst_val + list_base;
-        lr.base = sg.t0;
-        stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
-      } else {
-        stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
-      }
+  for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+  int ra, re;
+  wave_run<RW>(sg.t0, sg.t1, rw, ra, re);
+  if (col < a.d_out) {
+    if (staged) {
+      LdsRows lr;
+      lr.idx = lst_idx;
+      lr.val = lst_val;
+      lr.base = sg.t0;
+      stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, lr, ra, re, acc);
+    } else {
+      stream_rows_w4<T>(w.Wq + col / 8, row_dwords, w.scales + col / kW4Group, w.ng, rows, ra, re, acc);
     }
-    reduce_and_finish<T, RW>(acc, sg, seg_no, b, g, a.G, K, a.chunk, a.nstrips, a.partial, a.counters, ep, sh, lane,
-                             rw);
-    list_base += n;
-    f0 += sg.t1 - sg.t0;
-    sg.s += 1;
-    sg.t0 = 0;
-    seg_no += 1;
   }
+  reduce_and_finish<T, RW>(acc, sg.s, b, g, a.G, a.wps, a.partial, a.counters, a.nstrips, ep, sh, lane, rw);
 }
 
 // Round-to-nearest quantiser: one wave per row and 512 columns, a lane holds 8 columns, 16 lanes
