@@ -385,3 +385,48 @@ def test_adapter_cost_matches_printed_tflops():
     for model, L, D, orig, new in _rows("table19_adapter_tflops.txt"):
         extra = int(L) * 2 * int(D) ** 2 * 2048 / 1e12
         assert abs((float(new) - float(orig)) - extra) < 0.011, model
+
+
+# ------------------------------------------------------------------ SiLU and the unrounded select
+
+def test_silu_closed_form_values():
+    """SiLU(x) = x * sigmoid(x) at points where the sigmoid is a known rational: sigmoid(ln 3) = 3/4,
+    sigmoid(-ln 3) = 1/4, sigmoid(ln 2) = 2/3, sigmoid(0) = 1/2; limits x and 0 for large |x|; the
+    minimum of SiLU is -0.27846454276107... at x = -1.27846454276107... (root of 1 + e^-x (1 + x) = 0)."""
+    l3, l2 = math.log(3.0), math.log(2.0)
+    got = O.silu(np.array([0.0, l3, -l3, l2, -l2, 1.0]))
+    want = [0.0, 0.75 * l3, -0.25 * l3, (2.0 / 3.0) * l2, -(1.0 / 3.0) * l2, 1.0 / (1.0 + math.exp(-1.0))]
+    assert np.allclose(got, want, rtol=0, atol=1e-15)
+    assert abs(O.silu(np.array([40.0]))[0] - 40.0) < 1e-14            # x * (1 - e^-40 ...)
+    assert -1e-15 < O.silu(np.array([-40.0]))[0] <= 0.0               # -40 e^-40
+    x0 = -1.2784645427610737
+    assert abs(O.silu(np.array([x0]))[0] - x0 / (1.0 + math.exp(-x0))) < 1e-15
+    assert abs(O.silu(np.array([x0]))[0] + 0.27846454276107380) < 1e-12
+    xs = np.linspace(-6, 6, 2001)
+    assert np.all(O.silu(xs) >= O.silu(np.array([x0]))[0] - 1e-15)    # it is the minimum
+    # odd-part identity: SiLU(x) - SiLU(-x) = x
+    assert np.allclose(O.silu(xs) - O.silu(-xs), xs, rtol=0, atol=1e-14)
+
+
+def test_unrounded_select_matches_brute_force_sort_below_full_K():
+    """The fp64 (unrounded) layer run orders by |h| in fp64 with the lower index first among equals:
+    against a plain Python sort, K < d, with exact ties planted."""
+    rng = np.random.default_rng(17)
+    for d, K in ((12, 5), (64, 1), (257, 100), (1000, 999)):
+        h = rng.standard_normal(d)
+        h[rng.choice(d, d // 4, replace=False)] = rng.choice([0.5, -0.5, 2.0])      # ties, both signs
+        got = O._select(h, K, None)
+        brute = sorted(sorted(range(d), key=lambda i: (-abs(h[i]), i))[:K])
+        assert got.tolist() == brute
+        assert got.dtype == np.int32 and np.all(np.diff(got) > 0)
+    # and a layer run: every index set of the unrounded run is the brute-force set of its own stage input
+    shape = synth.LayerShape("pin", 64, 64, 32, 96, 16, "f16")
+    from tests import cases
+    case = cases.build_block_layer(shape, 0.5, seed=5, n_cal=256)
+    x = case.src.draw(1, seed=9)[0]
+    r = O.layer_forward(case.layer, x, rounded=False)
+    for hn, inn, K in (("h1", "idx1", case.layer.K1), ("h2", "idx2", case.layer.K2), ("h3", "idx3", case.layer.K3),
+                       ("h4", "idx4", case.layer.K4)):
+        h = r[hn]
+        assert K < h.size
+        assert r[inn].tolist() == sorted(sorted(range(h.size), key=lambda i: (-abs(h[i]), i))[:K])
