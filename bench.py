@@ -25,10 +25,29 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script scaled by a 1 GiB copy (profiles/*_hbm_traffic.txt).
-# Keyed by (config, batch, sparsity, form); other workloads have not been counted.
-MEASURED_TRAFFIC_BYTES = {(1, 1, 0.4, "explicit"): 63.2e6, (1, 1, 0.4, "shortcut"): 79.8e6}
+# HBM bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script scaled by a 1 GiB copy; the summaries under profiles/ carry the figure on a line
+# "traffic_bytes_per_launch: <number>", which is read back here (the counters cannot be collected from
+# inside an ordinary run).  Keyed by (config, batch, sparsity, form); other workloads have not been counted.
+TRAFFIC_SUMMARIES = {
+    (1, 1, 0.4, "shortcut"): "profiles/fused_topk_gemv_llama2_7b_layer_b1_s40_shortcut_form_hbm_traffic.txt",
+    (1, 1, 0.4, "explicit"): "profiles/gemv_rows_llama2_7b_layer_b1_s40_hbm_traffic.txt",
+}
+
+
+def measured_traffic(key):
+    """(bytes per launch, summary file) from the committed counter summary of this workload, or (None, None)."""
+    rel = TRAFFIC_SUMMARIES.get(key)
+    if rel is None:
+        return None, None
+    try:
+        with open(os.path.join(ROOT, rel)) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0]), rel
+    except OSError:
+        pass
+    return None, None
 
 CONFIGS = {
     1: dict(shape="llama2-7b", workload="LLaMA2-7B-shaped decoder layer, fp16, batch 1, 40% sparsity, "
@@ -299,7 +318,7 @@ def stack_report(args, api, torch, shape, cfg, dev):
     d, d_q, d_kv, d_ff = shape.d, shape.d_q, shape.d_kv, shape.d_ff
     d_qkv = d_q + 2 * d_kv
     p, B, n_layers = args.sparsity, args.batch, cfg["n_layers"]
-    from paper_2507_01299_amd import allocation, prepare
+    from paper_2507_01299_amd import allocation, synth
     K1, K2, K3, K4 = allocation.kept_counts(d, d_q, d_ff, p, 1.0, 1.0)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1299 * 1000 + 40)
@@ -321,7 +340,7 @@ def stack_report(args, api, torch, shape, cfg, dev):
         w = dict(Wqkv=gauss(d, d_qkv), Wo=gauss(d_q, d), Wgu=gauss(d, 2 * d_ff), Wdown=gauss(d_ff, d), A=A)
         weights.append(w)
         layers.append(api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, w["Wqkv"], w["Wo"], w["Wgu"],
-                                w["Wdown"], shape.dtype, rms_eps=prepare.RMS_EPS, shortcut_mlp=A))
+                                w["Wdown"], shape.dtype, rms_eps=synth.RMS_EPS, shortcut_mlp=A))
         Q_prev = Q_next
     torch.cuda.synchronize()
     env = torch.arange(1, d + 1, device=dev, dtype=torch.float32) ** -0.8
@@ -385,12 +404,14 @@ def stack_report(args, api, torch, shape, cfg, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=800)
-    ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=1, choices=sorted(CONFIGS))
     ap.add_argument("--sparsity", type=float, default=0.4)
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--nsets", type=int, default=8)
+    ap.add_argument("--replays", type=int, default=25,
+                    help="timed replays of the graph of --steps steps (at least 25); the value is their median")
     ap.add_argument("--alpha", default="1.0,1.0", metavar="A1,A3",
                     help="sparsity coefficients of h1 and h3 (h2, h4 follow from the block constraints)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -422,7 +443,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2507_01299_amd import api, prepare, synth
+    from paper_2507_01299_amd import api, offline, synth
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
@@ -456,13 +477,18 @@ def main():
     src = synth.activation_source(d, seed, latent=cfg["latent"])
     W = synth.layer_weights(shape, seed + 100)
     Xc = src.draw(cfg["n_cal"], seed + 1)
-    ops0 = prepare.block_layer_operands(shape, W, Xc, td, dev)
-    del W, Xc
+    # prepared through the library's own offline calls (second moments, folds and adapters on the matrix
+    # cores; the eigen-solver in between is torch's, on the host for widths where the device solver is slow)
+    Wdev = {k: torch.as_tensor(v).to(dev).to(td).contiguous() for k, v in W.items()}
+    Xcd = torch.as_tensor(Xc).to(dev).to(td).contiguous()
+    ops0 = offline.prepare_shortcut_layer(shape, Wdev, Xcd, rms_eps=synth.RMS_EPS,
+                                          solver_device="cpu" if d > 4096 else None)
+    del W, Xc, Wdev, Xcd
     x = torch.as_tensor(src.draw(B, synth.seed_for(args.config, 5))).to(dev).to(td).contiguous()
     x_explicit = x
     shortcut_form = args.form == "shortcut"
     if shortcut_form:      # the stream arrives in the attention block's basis
-        x = (x.double() @ ops0["Q_attn"].double()).to(td).contiguous()
+        x = (x.double() @ ops0["Q_attn32"].double()).to(td).contiguous()
     log(f"canonical layer prepared in {time.time() - t0:.1f}s")
 
     # ---- further weight sets: the folded weight of a Gaussian W under an orthogonal Q is again
@@ -484,10 +510,10 @@ def main():
     def make_layer(s, form_shortcut):
         if form_shortcut:
             return api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, s["Wqkv"], s["Wo"], s["Wgu"],
-                             s["Wdown"], shape.dtype, rms_eps=prepare.RMS_EPS, shortcut_attn=s["shortcut_attn"],
+                             s["Wdown"], shape.dtype, rms_eps=synth.RMS_EPS, shortcut_attn=s["shortcut_attn"],
                              shortcut_mlp=s["shortcut_mlp"])
         return api.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, s["Wqkv"], s["Wo"], s["Wgu"],
-                         s["Wdown"], shape.dtype, Q_attn=s["Q_attn"], Q_mlp=s["Q_mlp"], rms_eps=prepare.RMS_EPS)
+                         s["Wdown"], shape.dtype, Q_attn=s["Q_attn"], Q_mlp=s["Q_mlp"], rms_eps=synth.RMS_EPS)
 
     layers = [make_layer(s, shortcut_form) for s in sets]
     # the other form on the same weight sets (timing only: the weights are random either way)
@@ -527,38 +553,49 @@ def main():
             fn()
         return g
 
-    def all_layers():
-        for L in layers:
-            api.layer_forward(L, x, out, ws)
+    # The timed unit is ONE graph of exactly `steps` steps (step i uses weight set i mod nsets); it is replayed
+    # `replays` times, every replay bracketed by HIP events on the launch stream, and the figure reported is the
+    # median replay (p10 / p90 beside it).  One event record costs a few microseconds per replay, i.e. per
+    # `steps` steps.
+    K_steps = max(1, args.steps)
+    replays = max(25, args.replays)
 
-    g_layer = capture(all_layers)
-    replays = max(1, args.steps // nsets)
-    for _ in range(max(1, args.warmup // nsets)):
+    def timed_steps():
+        for i in range(K_steps):
+            api.layer_forward(layers[i % nsets], x, out, ws)
+
+    def replay_stats(g, n):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        g.replay()
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(n):
+            g.replay()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / K_steps for i in range(n))
+        return dict(median=per[n // 2], p10=per[n // 10], p90=per[(n * 9) // 10], min=per[0], max=per[-1], n=n)
+
+    g_layer = capture(timed_steps)
+    for _ in range(max(1, -(-args.warmup // K_steps))):
         g_layer.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(replays):
-        g_layer.replay()
-    torch.cuda.synchronize()
-    graph_s = time.perf_counter() - t0
-    graph_steps = replays * nsets
-    graph_us = graph_s / graph_steps * 1e6
+    st_graph = replay_stats(g_layer, replays)
+    graph_wall_s = time.perf_counter() - t0
+    graph_us = st_graph["median"]
+    graph_steps = K_steps
 
-    x_other = x_explicit if shortcut_form else (x.double() @ ops0["Q_attn"].double()).to(td).contiguous()
+    x_other = x_explicit if shortcut_form else (x.double() @ ops0["Q_attn32"].double()).to(td).contiguous()
 
-    def all_layers_other():
-        for L in layers_other:
-            api.layer_forward(L, x_other, out, ws)
+    def other_steps():
+        for i in range(K_steps):
+            api.layer_forward(layers_other[i % nsets], x_other, out, ws)
 
-    g_other = capture(all_layers_other)
-    for _ in range(max(1, args.warmup // nsets)):
-        g_other.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(replays):
-        g_other.replay()
-    torch.cuda.synchronize()
-    other_us = (time.perf_counter() - t0) / graph_steps * 1e6
+    g_other = capture(other_steps)
+    g_other.replay()
+    other_us = replay_stats(g_other, replays)["median"]
+    del g_other
 
     # ---- the dominant kernel alone: the four column-sparse projections of a layer on real
     # activations / index sets (taken from a traced run of set 0), HIP events on the launch stream
@@ -586,7 +623,7 @@ def main():
             for wn, hn, inn, yn, K, dout in proj:
                 api.sparse_gemv(s[wn], trace[hn], trace[inn], ys[yn], shape.dtype, ws)
 
-    reps = max(1, args.steps // nsets)
+    reps = max(3, min(64, args.steps // nsets))
     sparse_launch_us = event_time_us(sparse_all, 4 * nsets, reps)
     standalone_launch_us = sparse_launch_us
     stage_us = None
@@ -621,15 +658,7 @@ def main():
             # In this form the step IS four launches of the fused kernel and nothing else, so the launch
             # time is the step time / 4, taken with HIP events around graph replays on the launch stream
             # (the per-stage events above each add the cost of an event record to their interval).
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            g_layer.replay()
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(replays):
-                g_layer.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            sparse_launch_us = e0.elapsed_time(e1) * 1e3 / (replays * nsets * 4)
+            sparse_launch_us = graph_us / 4.0
     # rows a launch has to read: the kept rows at batch 1, the union of the tokens' kept rows otherwise
     U = [int(torch.unique(trace[n]).numel()) for n in ("idx1", "idx2", "idx3", "idx4")]
     sel_bytes_layer = 2 * (U[0] * d_qkv + U[1] * d + U[2] * 2 * d_ff + U[3] * d)
@@ -703,7 +732,7 @@ def main():
                     shortcut_mlp=vals(s0["shortcut_mlp"]).astype(np.float64)) if shortcut_form else
                dict(Q_attn=vals(s0["Q_attn"]).astype(np.float64), Q_mlp=vals(s0["Q_mlp"]).astype(np.float64)))
         OL = O.Layer(d, d_q, d_kv, d_ff, shape.head_dim, K1, K2, K3, K4, Wqkv=vals(s0["Wqkv"]), Wo=vals(s0["Wo"]),
-                     Wgu=vals(s0["Wgu"]), Wdown=vals(s0["Wdown"]), rms_eps=prepare.RMS_EPS, dtype=shape.dtype, **rot)
+                     Wgu=vals(s0["Wgu"]), Wdown=vals(s0["Wdown"]), rms_eps=synth.RMS_EPS, dtype=shape.dtype, **rot)
         xs = O.decode16(bits(x), shape.dtype)
         t0 = time.perf_counter()
         r = O.layer_forward(OL, xs[0])
@@ -721,7 +750,10 @@ def main():
                           f"(numpy, {threads} BLAS threads, {os.cpu_count()} host cpus)",
                    idx1_matches_oracle=idx_equal)
 
-    all_bytes_layer = sel_bytes_layer + 2 * 2 * d * d       # + the two explicit rotations
+    all_bytes_layer = sel_bytes_layer + 2 * 2 * d * d       # + the two d x d rotations / shortcut adapters
+    traffic, traffic_src = (measured_traffic((args.config, B, p, args.form)) if args.alpha == "1.0,1.0" else (None, None))
+    sel_GBs = sel_bytes_layer / (graph_us * 1e-6) / 1e9
+    all_GBs = all_bytes_layer / (graph_us * 1e-6) / 1e9
     report = {
         "metric": "us_per_decoder_layer",
         "value": round(graph_us, 3),
@@ -742,11 +774,18 @@ def main():
                             if shortcut_form else "explicit rotation mat-vecs in front of q|k|v and gate|up"),
                    "shape": shape.name, "batch": B, "sparsity": p, "K": [K1, K2, K3, K4], "union_rows": U,
                    "weight_sets": nsets,
-                   "launch": "one HIP graph of larosa_layer_forward per weight set"},
+                   "launch": f"one HIP graph of {K_steps} larosa_layer_forward steps (weight set i mod {nsets}), replayed "
+                             f"{replays} times; value = median replay"},
         "roofline": {"bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": (MEASURED_TRAFFIC_BYTES.get((args.config, B, p, args.form))
-                                 if args.alpha == "1.0,1.0" else None),
+                     "traffic": traffic,
+                     "traffic_source": (None if traffic_src is None else
+                                        f"{traffic_src} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, "
+                                        "scaled by a 1 GiB copy; not collected in this run)"),
+                     # the same step time against the two byte counts of the whole layer
+                     "selected_row_bytes_per_layer": sel_bytes_layer,
+                     "achieved_selected_rows": round(sel_GBs, 1), "frac_selected_rows": round(sel_GBs / HBM_PEAK_GBS, 4),
+                     "achieved_all_bytes": round(all_GBs, 1), "frac_all_bytes": round(all_GBs / HBM_PEAK_GBS, 4),
                      "kernel": (("fused_topk_gemv_kernel: the 4 Top-K + column-sparse projections of a layer step "
                                  + ("(two of them carry a residual adapter in the same launch; its bytes are counted), "
                                     if shortcut_form else ", ")
@@ -765,6 +804,8 @@ def main():
             ("explicit_rotation_form_us_per_layer" if shortcut_form else "shortcut_form_us_per_layer"):
                 round(other_us, 2),
             "graph_us_per_layer": round(graph_us, 2),
+            "graph_replay_us_per_layer": {k: (round(v, 3) if k != "n" else v) for k, v in st_graph.items()},
+            "graph_replays_wall_s": round(graph_wall_s, 3),
             "tokens_per_s_32_layers": round(1e6 / (graph_us * 32), 1),
             "selected_row_bytes_per_layer": sel_bytes_layer,
             "layer_GBs_on_selected_rows": round(sel_bytes_layer / (graph_us * 1e-6) / 1e9, 1),

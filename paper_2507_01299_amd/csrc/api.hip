@@ -21,6 +21,7 @@ constexpr size_t kCounterSlots = 4096;                        // arrival counter
 constexpr size_t kCounterWords = kCounterSlots * kCounterStride;
 constexpr size_t kCounterBytes = kCounterWords * sizeof(unsigned);
 constexpr int kMaxTopkD = 32768;
+constexpr size_t kHistBytes = kHistWords * sizeof(unsigned);
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -353,6 +354,7 @@ size_t larosa_layer_workspace_bytes(const larosa_layer* L, int B) {
   const int Ks[] = {L->K1, L->K2, L->K3, L->K4};
   for (int k : Ks) s += round_up(Bz * k * sizeof(int32_t), 256) + 256;
   if (B > 1) s += round_up(Bz * max3(L->d, L->d_q, L->d_ff) * E, 256) + 256;   // masked activations
+  s += round_up(kHistBytes, 256) + 256;                                       // key histograms of the MLP vector (batch 1)
   return s;
 }
 
@@ -414,6 +416,9 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
   int32_t* idx3 = bufidx(T.idx3, L->K3);
   int32_t* idx4 = bufidx(T.idx4, L->K4);
   uint16_t* masked = B > 1 ? static_cast<uint16_t*>(cv.take(Bz * max3(d, d_q, d_ff) * 2)) : nullptr;
+  // batch 1: the gate|up launch's finishing workgroups build the key histograms of the MLP vector, the down
+  // projection reads its threshold off them; the o projection's launch (always between two uses) clears them
+  unsigned* hist4 = (B == 1 && tuning().fused && tuning().hinted) ? static_cast<unsigned*>(cv.take(kHistBytes)) : nullptr;
   if (!cv.ok) return LAROSA_EWORKSPACE;
   const uint16_t* x = static_cast<const uint16_t*>(x_in);
 
@@ -553,9 +558,12 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
     auto fused = [&](int mode, const uint16_t* src, const void* W, uint16_t* y, int d_in, int d_out, int K,
                      const uint16_t* residual, uint16_t* y_pre, uint16_t* h_out, int32_t* idx_out,
                      const void* nscale, const void* sideA = nullptr, const uint16_t* side_x = nullptr,
-                     uint16_t* side_y = nullptr, int pair_cols = 0, uint16_t* pair_out = nullptr) -> int {
+                     uint16_t* side_y = nullptr, int pair_cols = 0, uint16_t* pair_out = nullptr,
+                     const unsigned* hist_in = nullptr, unsigned* hist_out = nullptr, unsigned* zero = nullptr) -> int {
       FusedArgs a{};
       a.pair_cols = pair_cols; a.pair_out = pair_out;
+      a.hist_in = hist_in; a.hist_out = hist_out; a.hist_weight = 1;
+      a.zero_ptr = zero; a.zero_words = zero ? static_cast<int>(kHistBytes / sizeof(unsigned)) : 0;
       if (sideA) {
         a.side.W = static_cast<const uint16_t*>(sideA);
         a.side.h = side_x; a.side.y = side_y;
@@ -575,31 +583,36 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
     // the block's first projection; its shortcut adapter (sc: A, dst) shares the launch
     auto first = [&](const uint16_t* src, const void* Q, const void* scale, uint16_t* h, void* h_traced, const void* W,
                      uint16_t* y, int d_out, int K, int32_t* idx_traced, const void* scA, uint16_t* sc_dst,
-                     int pair_cols, uint16_t* pair_out) -> int {
+                     int pair_cols, uint16_t* pair_out, unsigned* hist_out) -> int {
       if (Q) {
         if (int rc = block_input(src, Q, scale, h)) return rc;
         mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
         return fused(kSrcPlain, h, W, y, d, d_out, K, nullptr, nullptr, nullptr, idx_traced, nullptr, scA, src,
-                     sc_dst, pair_cols, pair_out);
+                     sc_dst, pair_cols, pair_out, nullptr, hist_out);
       }
       mark(d_out == d_qkv && W == L->Wqkv ? 1 : 4);
       return fused(norm ? kSrcNorm : kSrcPlain, src, W, y, d, d_out, K, nullptr, nullptr,
-                   static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst, pair_cols, pair_out);
+                   static_cast<uint16_t*>(h_traced), idx_traced, scale, scA, src, sc_dst, pair_cols, pair_out, nullptr,
+                   hist_out);
     };
     if (part != kAfterAttention) {
       LAROSA_TRY(first(x, L->Q_attn, L->rms_attn, h1, T.h1, L->Wqkv, qkv, d_qkv, L->K1, T.idx1,
-                       s1 ? L->shortcut_attn : nullptr, s1, 0, nullptr));
+                       s1 ? L->shortcut_attn : nullptr, s1, 0, nullptr, nullptr));
       mark(2);
       if (part == kUntilQkv) return LAROSA_OK;
     }
     LAROSA_TRY(fused(attn ? kSrcPlain : kSrcGqa, attn ? attn : qkv, L->Wo, x1, d_q, d, L->K2, s1 ? s1 : x,
-                     static_cast<uint16_t*>(T.o), static_cast<uint16_t*>(T.h2), T.idx2, nullptr));
+                     static_cast<uint16_t*>(T.o), static_cast<uint16_t*>(T.h2), T.idx2, nullptr, nullptr, nullptr, nullptr,
+                     0, nullptr, nullptr, nullptr, hist4));
     mark(3);
     // gate|up with paired strips: the workgroups that finish it also store h4 = R(SiLU(gate) * up)
     LAROSA_TRY(first(x1, L->Q_mlp, L->rms_mlp, h3, T.h3, L->Wgu, gu, 2 * d_ff, L->K3, T.idx3, L->shortcut_mlp, s2, d_ff,
-                     h4));
+                     h4, hist4));
     mark(5);
-    if (d_ff <= tuning().fused_max_width) {
+    if (hist4) {
+      LAROSA_TRY(fused(kSrcPlain, h4, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
+                       nullptr, T.idx4, nullptr, nullptr, nullptr, nullptr, 0, nullptr, hist4));
+    } else if (d_ff <= tuning().fused_max_width) {
       LAROSA_TRY(fused(kSrcPlain, h4, L->Wdown, x2, d_ff, d, L->K4, s2 ? s2 : x1, static_cast<uint16_t*>(T.down),
                        nullptr, T.idx4, nullptr));
     } else {
@@ -926,6 +939,10 @@ int larosa_set_tuning(int key, int value) {
     case 8:
       if (value < 8 || value > kMaxTopkD) return LAROSA_EINVAL;
       tuning().fused_max_width = value;
+      return LAROSA_OK;
+    case 9:
+      if (value < 0 || value > 1) return LAROSA_EINVAL;
+      tuning().hinted = value;
       return LAROSA_OK;
     default:
       return LAROSA_EINVAL;

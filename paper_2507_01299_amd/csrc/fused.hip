@@ -40,23 +40,48 @@ __device__ __forceinline__ uint2 load_source4(const FusedArgs& a, int b, int i) 
 }
 
 // Projection whose input vector arrives with its key histograms (FusedArgs::hist_in): the threshold
-// comes from two small reads by wave 0, every workgroup then only classifies the vector's elements
-// against it, ranks them with one block prefix sum and keeps its own ranks' (row, coefficient) pairs.
-// The vector sits in LDS, transposed ([group of 4][lane], so lane t's elements [tE, (t+1)E) are read
-// without bank conflicts), not in registers: one instantiation serves every width up to kHintMaxWidth.
+// comes from two small reads by wave 0; every workgroup then only classifies the vector's elements
+// against it, ranks them and keeps its own ranks' rows.
+//
+// The vector sits in LDS in its natural order (one instantiation serves every width up to kHintMaxWidth),
+// and lane t owns the groups of four elements t, t + NT, t + 2 NT, ...: "slab" q4 is the NT * 4
+// consecutive elements whose groups the lanes hold at step q4.  A kept element's rank is the number of
+// kept elements in earlier slabs, plus those of earlier waves in its slab, plus those of earlier lanes
+// in its wave (a wave-level prefix sum per slab), plus those before it in its group.  A workgroup's
+// contiguous rank range therefore falls on many consecutive lanes, a few elements each: building the
+// row list is parallel work, not a long walk by a few lanes.
+constexpr int kHintSlabs = kHintMaxWidth / (8 * 64 * 4);   // 16 slabs of 2048 elements
+
 struct HintShared {
-  uint2 vec[kHintMaxWidth / 4];   // group q4 of lane t at [q4 * NT + t]
-  unsigned wave_gt[16], wave_eq[16];
+  uint2 vec[kHintMaxWidth / 4];          // group i / 4 of the vector
+  unsigned tot[kHintSlabs * 8];          // per (slab, wave): kept-by-magnitude count | threshold ties << 16
   unsigned T, r;
 };
 
-template <typename T, int RW>
-__global__ __launch_bounds__(RW * 64) void fused_hinted_gemv_kernel(FusedArgs a) {
-  constexpr int NT = RW * 64;
+// The rows of a workgroup's ranks as indices in LDS, their coefficients read from the vector in LDS.
+template <typename T>
+struct LdsRowsOfVector {
+  const int* idx;
+  const uint16_t* vec;
+  int base;                  // rank of entry 0
+  __device__ __forceinline__ void batch(int t, int re, int lane, int (&j)[kUnroll], float (&c)[kUnroll]) const {
+    const int u0 = lane & (kUnroll - 1);
+    const int myj = idx[min(t + u0, re - 1) - base];
+    const float myc = (t + u0 < re) ? T::to_f32(vec[myj]) : 0.f;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      j[u] = __builtin_amdgcn_readlane(myj, u);
+      c[u] = __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(__float_as_uint(myc)), u)));
+    }
+  }
+};
+
+template <typename T, int NS>   // NS slabs (2048 elements each) cover the vector
+__global__ __launch_bounds__(512) void fused_hinted_gemv_kernel(FusedArgs a) {
+  constexpr int RW = 8, NT = RW * 64;
   __shared__ HintShared hs;
   __shared__ GemvShared<RW> sh;
   __shared__ int lst_idx[kFusedChunkMax];
-  __shared__ float lst_val[kFusedChunkMax];
 
   LAROSA_STAMP(0);
   const int tid = threadIdx.x;
@@ -67,104 +92,121 @@ __global__ __launch_bounds__(RW * 64) void fused_hinted_gemv_kernel(FusedArgs a)
   clear_words<NT>(a, g);
   const int d_in = a.g.d_in;
   const int K = a.g.K;
-  const int E4 = (d_in + NT * 4 - 1) / (NT * 4);   // groups of 4 elements per lane (<= 16)
-  const int base = tid * E4 * 4;
 
-  // ---- the vector into LDS; meanwhile wave 0 reads the threshold off the histograms
-  for (int q4 = 0; q4 < E4; ++q4) {
-    const int i = base + q4 * 4;
-    hs.vec[q4 * NT + tid] = i < d_in ? load_source4(a, b, i) : make_uint2(0u, 0u);
+  // ---- wave 0 reads the threshold off the histograms (two dependent reads, the first issued before
+  // anything else); every lane's groups of the vector are loaded at once, kept in registers for the
+  // classification and copied to LDS for the row loop (padding of the last slab: zeros)
+  const unsigned* hist = a.hist_in + static_cast<size_t>(b) * kHistWords;
+  uint4 coarse = make_uint4(0u, 0u, 0u, 0u);
+  if (rw == 0) coarse = *hist_coarse_ptr(hist, lane);
+  uint2 vq[NS];
+#pragma unroll
+  for (int q4 = 0; q4 < NS; ++q4) {
+    vq[q4] = make_uint2(0u, 0u);
+    const int i = (q4 * NT + tid) * 4;
+    if (i < d_in) vq[q4] = load_source4(a, b, i);
+  }
+  int bin1 = 0;
+  unsigned above1 = 0;
+  uint2 fine = make_uint2(0u, 0u);
+  if (rw == 0) {
+    hist_coarse_step(coarse, K, lane, bin1, above1);
+    fine = *hist_fine_ptr(hist, bin1, lane);
+  }
+#pragma unroll
+  for (int q4 = 0; q4 < NS; ++q4) {
+    {
+      hs.vec[q4 * NT + tid] = vq[q4];
+      const int i = (q4 * NT + tid) * 4;
+      if (a.h_out && g == 0 && i < d_in) *reinterpret_cast<uint2*>(a.h_out + static_cast<size_t>(b) * d_in + i) = vq[q4];
+    }
   }
   if (rw == 0) {
     unsigned Tk, r;
-    threshold_from_histograms(a.hist_in + static_cast<size_t>(b) * kHistWords, K, lane, Tk, r);
+    hist_fine_step(fine, K, bin1, above1, lane, Tk, r);
     if (lane == 0) {
       hs.T = Tk;
       hs.r = r;
-    }
-  }
-  if (a.h_out && g == 0) {
-    for (int q4 = 0; q4 < E4; ++q4) {
-      const int i = base + q4 * 4;
-      if (i < d_in) *reinterpret_cast<uint2*>(a.h_out + static_cast<size_t>(b) * d_in + i) = hs.vec[q4 * NT + tid];
     }
   }
   __syncthreads();
   LAROSA_STAMP(1);
   const unsigned Tk = hs.T, r = hs.r;
 
-  // ---- classify this lane's elements, rank them by a block prefix sum
-  unsigned long long m_gt = 0, m_eq = 0;
-  for (int q4 = 0; q4 < E4; ++q4) {
-    const uint2 v = hs.vec[q4 * NT + tid];
+  // ---- classify: per slab a 4-bit mask of keys > T and of keys == T, then the wave-level prefix of their counts
+  unsigned cls[NS];      // gt mask | eq mask << 4, later also the exclusive wave prefix: gt << 8 | eq << 16
+  unsigned cnt[NS];
+#pragma unroll
+  for (int q4 = 0; q4 < NS; ++q4) {
+    const uint2 v = vq[q4];
     const unsigned k0 = v.x & 0x7FFFu, k1 = (v.x >> 16) & 0x7FFFu, k2 = v.y & 0x7FFFu, k3 = (v.y >> 16) & 0x7FFFu;
     const unsigned gt = (k0 > Tk ? 1u : 0u) | (k1 > Tk ? 2u : 0u) | (k2 > Tk ? 4u : 0u) | (k3 > Tk ? 8u : 0u);
     const unsigned eq = (k0 == Tk ? 1u : 0u) | (k1 == Tk ? 2u : 0u) | (k2 == Tk ? 4u : 0u) | (k3 == Tk ? 8u : 0u);
-    m_gt |= static_cast<unsigned long long>(gt) << (4 * q4);
-    m_eq |= static_cast<unsigned long long>(eq) << (4 * q4);
+    cls[q4] = gt | (eq << 4);
+    cnt[q4] = static_cast<unsigned>(__popc(gt)) | (static_cast<unsigned>(__popc(eq)) << 16);   // a wave: <= 256 each
   }
-  // padding (zeros past the end of the vector) can only meet T == 0, as ties at the highest indices: never kept
-  TopkLaneT<unsigned long long> st;
-  st.T = Tk;
-  st.r = r;
-  st.m_gt = m_gt;
-  st.m_eq = m_eq;
-  st.n_gt = popc_mask(m_gt);
-  st.n_eq = popc_mask(m_eq);
-  {
-    const unsigned packed = st.n_gt | (st.n_eq << 16);      // a wave holds at most 64 * 64 elements
-    const unsigned incl = wave_scan_inclusive(packed, lane);
-    if (lane == 63) {
-      hs.wave_gt[rw] = incl & 0xFFFFu;
-      hs.wave_eq[rw] = incl >> 16;
-    }
-    __syncthreads();
-    unsigned gt_before = (incl - packed) & 0xFFFFu, eq_before = (incl - packed) >> 16;
 #pragma unroll
-    for (int w = 0; w < RW; ++w) {
-      const unsigned wg = hs.wave_gt[w], we = hs.wave_eq[w];
-      gt_before += (w < rw) ? wg : 0u;
-      eq_before += (w < rw) ? we : 0u;
+  for (int q4 = 0; q4 < NS; ++q4) {
+    {
+      const unsigned incl = wave_scan_inclusive(cnt[q4], lane);
+      if (lane == 63) hs.tot[q4 * RW + rw] = incl;
+      const unsigned excl = incl - cnt[q4];
+      cls[q4] |= ((excl & 0xFFu) << 8) | ((excl >> 16) << 16);   // below 256: 8 bits each
     }
-    st.gt_before = gt_before;
-    st.eq_before = eq_before;
+  }
+  __syncthreads();
+  // every wave: exclusive prefix of the (slab, wave) totals in that order; entry e = slab * 8 + wave sits in
+  // lane e / 2, half e % 2 (at most 128 entries)
+  unsigned pre_gt[2], pre_eq[2], tot2[2] = {0u, 0u};
+  {
+    if (2 * lane < NS * RW) {
+      const uint2 tt = *reinterpret_cast<const uint2*>(&hs.tot[2 * lane]);
+      tot2[0] = tt.x;
+      tot2[1] = tt.y;
+    }
+    const unsigned g0 = tot2[0] & 0xFFFFu, g1 = tot2[1] & 0xFFFFu, e0 = tot2[0] >> 16, e1 = tot2[1] >> 16;
+    const unsigned sg_ = wave_scan_inclusive(g0 + g1, lane) - (g0 + g1);
+    const unsigned se_ = wave_scan_inclusive(e0 + e1, lane) - (e0 + e1);
+    pre_gt[0] = sg_; pre_gt[1] = sg_ + g0;
+    pre_eq[0] = se_; pre_eq[1] = se_ + e0;
   }
   LAROSA_STAMP(2);
 
-  // ---- this workgroup's ranks: (row, coefficient) pairs into LDS; workgroup 0 also writes the index list
+  // ---- this workgroup's ranks: row indices into LDS; workgroup 0 also writes the whole index list.
+  // A wave's share of a slab holds a contiguous run of ranks: waves whose run misses the workgroup's
+  // range skip the slab (all but one or two of the wave-slab pairs).
   const Segment sg = segment_of(g, a.g.wps, a.g.chunk, K);
   const int n = sg.t1 - sg.t0;
   int32_t* idx_out = (a.idx_out && g == 0) ? a.idx_out + static_cast<size_t>(b) * K : nullptr;
-  const int p0 = static_cast<int>(st.first_rank()), p1 = static_cast<int>(st.end_rank());
-  if (idx_out || (p0 < sg.t1 && p1 > sg.t0)) {
-    // threshold ties of this lane that are kept: its first (r - eq_before) ones
-    unsigned long long eq_keep = m_eq;
-    const int want = static_cast<int>(r) - static_cast<int>(st.eq_before);
-    if (want < static_cast<int>(st.n_eq)) {
-      unsigned long long m = m_eq;
-      eq_keep = 0;
-      for (int i = 0; i < want; ++i) {
-        const unsigned long long low = m & (0ull - m);
-        eq_keep |= low;
-        m ^= low;
+#pragma unroll
+  for (int q4 = 0; q4 < NS; ++q4) {
+    {
+      const int ent = q4 * RW + rw;
+      // the kept elements before this wave's share of the slab, from the lane that holds the entry
+      const unsigned bg = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>((ent & 1) ? pre_gt[1] : pre_gt[0]), ent >> 1));
+      const unsigned be = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>((ent & 1) ? pre_eq[1] : pre_eq[0]), ent >> 1));
+      const unsigned tw = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>((ent & 1) ? tot2[1] : tot2[0]), ent >> 1));
+      const int first = static_cast<int>(bg + min(be, r));                                     // rank of the wave's first kept element
+      const int end = static_cast<int>(bg + (tw & 0xFFFFu) + min(be + (tw >> 16), r));         // one past its last
+      if (idx_out || (first < sg.t1 && end > sg.t0)) {   // uniform over the wave
+        const unsigned c = cls[q4];
+        const unsigned gt = c & 0xFu, eq = (c >> 4) & 0xFu;
+        unsigned gt_before = bg + ((c >> 8) & 0xFFu), eq_before = be + (c >> 16);
+        const int i0 = (q4 * NT + tid) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool is_gt = (gt >> j) & 1u, is_eq = (eq >> j) & 1u;
+          const bool kept = is_gt || (is_eq && eq_before < r);       // ties: the first r in index order
+          const int pos = static_cast<int>(gt_before + min(eq_before, r));
+          if (kept) {
+            if (idx_out) idx_out[pos] = i0 + j;
+            const int e = pos - sg.t0;
+            if (static_cast<unsigned>(e) < static_cast<unsigned>(n)) lst_idx[e] = i0 + j;
+          }
+          gt_before += is_gt ? 1u : 0u;
+          eq_before += is_eq ? 1u : 0u;
+        }
       }
-    }
-    const unsigned long long kept = m_gt | eq_keep;
-    unsigned long long left = kept;
-    int pos = p0;
-    while (left) {                         // kept elements of the lane in index order
-      const int q = __builtin_ctzll(left);
-      left &= left - 1;
-      const uint2 v = hs.vec[(q >> 2) * NT + tid];
-      const unsigned w = (q & 2) ? v.y : v.x;
-      const uint16_t bits = static_cast<uint16_t>((q & 1) ? (w >> 16) : (w & 0xFFFFu));
-      if (idx_out) idx_out[pos] = base + q;
-      const int e = pos - sg.t0;
-      if (static_cast<unsigned>(e) < static_cast<unsigned>(n)) {
-        lst_idx[e] = base + q;
-        lst_val[e] = T::to_f32(bits);
-      }
-      ++pos;
     }
   }
   LAROSA_STAMP(3);
@@ -174,9 +216,9 @@ __global__ __launch_bounds__(RW * 64) void fused_hinted_gemv_kernel(FusedArgs a)
   // ---- stream the kept rows of this workgroup's ranks
   const Epilogue ep{a.g.y, a.g.rms_src, a.g.rms_eps, a.g.residual, a.g.y_pre, d_in, a.g.d_out, a.pair_cols, a.pair_out,
                     a.hist_out, a.hist_col0, a.hist_col1, a.hist_weight};
-  LdsRows rows;
+  LdsRowsOfVector<T> rows;
   rows.idx = lst_idx;
-  rows.val = lst_val;
+  rows.vec = reinterpret_cast<const uint16_t*>(hs.vec);
   rows.base = sg.t0;
   bool col_valid;
   const int col = strip_lane_col(sg.s, lane, a.g.d_out, a.pair_cols, col_valid);
@@ -344,7 +386,14 @@ template <typename T>
 hipError_t launch_hinted(const FusedArgs& a, hipStream_t st) {
   if (a.side_G > 0 || a.src_mode == kSrcNorm || a.g.d_in > kHintMaxWidth) return hipErrorInvalidValue;
   dim3 grid(a.g.G, a.g.B), block(8 * 64);
-  hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 8>), grid, block, 0, st, a);
+  const int ns = (a.g.d_in + 2047) / 2048;
+  if (ns <= 2) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 2>), grid, block, 0, st, a);
+  else if (ns <= 4) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 4>), grid, block, 0, st, a);
+  else if (ns <= 6) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 6>), grid, block, 0, st, a);
+  else if (ns <= 8) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 8>), grid, block, 0, st, a);
+  else if (ns <= 12) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 12>), grid, block, 0, st, a);
+  else if (ns <= 14) hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 14>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((fused_hinted_gemv_kernel<T, 16>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 

@@ -46,6 +46,7 @@ struct Tuning {
   int w4_wide_min_cols = 32768;   // 4-bit kernel: narrowest output that uses the 2048-column geometry
   int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
   int side_g = 0;             // workgroups of that adapter; 0 = by size (both jobs resident at once: at most 512 slots)
+  int hinted = 1;             // decoder layer: 1 = the down projection takes its threshold from histograms that the gate|up launch builds
 };
 Tuning& tuning();
 
@@ -103,6 +104,8 @@ struct FusedArgs {
   unsigned* zero_ptr;         // nullable: zero_words words that this launch clears (histograms a later launch fills)
   int zero_words;
 };
+constexpr int kHistCoarse = 256;                   // histogram layout: [0, 256) top 8 key bits, [256 + key] every 15-bit key
+constexpr int kHistWords = kHistCoarse + 32768;
 constexpr int kHintMaxWidth = 32768;   // widest input vector of the launch form that takes hist_in
 // pair_cols > 0: strips are 256 channels of gate and of up each (see FusedArgs)
 GemvPlan plan_fused(int d_out, int K, int g_hint = 0, int pair_cols = 0);

@@ -23,6 +23,7 @@
 #pragma once
 #include <cstddef>
 
+#include "kernels.hpp"
 #include "numeric.hpp"
 
 namespace larosa {
@@ -237,17 +238,23 @@ __device__ __forceinline__ TopkLaneT<typename LaneMask<E>::type> block_select(co
 // 8 key bits, hist[256 + key] every 15-bit key (the workgroups that store the vector's strips add their
 // elements with device atomics).  The threshold then costs two small dependent reads by one wave instead
 // of two histogram passes over the vector in every workgroup.
-constexpr int kHistCoarse = 256;
-constexpr int kHistWords = kHistCoarse + 32768;
 
-// Threshold key T and tie quota r = K - #{key > T} from such histograms; called by all 64 lanes of one
-// wave, result in every lane.  1 <= K <= number of counted elements.
-__device__ __forceinline__ void threshold_from_histograms(const unsigned* __restrict__ hist, int K, int lane,
-                                                          unsigned& T, unsigned& r) {
-  const uint4 v = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);   // bins 255 - 4 lane - q in .w .z .y .x
+// Threshold key T and tie quota r = K - #{key > T} from such histograms, in two steps so that the caller
+// can issue the loads where it wants them (the second read depends on the first step's result); all 64
+// lanes of one wave take part, results in every lane.  1 <= K <= number of counted elements.
+// Lane's words: coarse bins 255 - 4 lane - q (q = 0..3) are hist[252 - 4 lane + (3 - q)], one 16-byte read.
+__device__ __forceinline__ const uint4* hist_coarse_ptr(const unsigned* hist, int lane) {
+  return reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);
+}
+// fine bins 127 - 2 lane, 126 - 2 lane of coarse bin `bin1`: one 8-byte read
+__device__ __forceinline__ const uint2* hist_fine_ptr(const unsigned* hist, int bin1, int lane) {
+  return reinterpret_cast<const uint2*>(hist + kHistCoarse + bin1 * 128 + 126 - 2 * lane);
+}
+// step 1: the coarse bin that holds the K-th largest key, and the count above it
+__device__ __forceinline__ void hist_coarse_step(const uint4& v, int K, int lane, int& bin1, unsigned& above1) {
   const unsigned c[4] = {v.w, v.z, v.y, v.x};
   const unsigned local = (c[0] + c[1]) + (c[2] + c[3]);
-  unsigned need = static_cast<unsigned>(K);
+  const unsigned need = static_cast<unsigned>(K);
   unsigned run = wave_scan_inclusive(local, lane) - local;
   int cand = -1;
   unsigned cand_above = 0;
@@ -260,16 +267,19 @@ __device__ __forceinline__ void threshold_from_histograms(const unsigned* __rest
       cand_above = before;
     }
   }
-  unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
-  int src = found ? __builtin_ctzll(found) : 0;
-  const int bin1 = max(0, __builtin_amdgcn_readlane(cand, src));
-  const unsigned above1 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
-  const uint2 f = *reinterpret_cast<const uint2*>(hist + kHistCoarse + bin1 * 128 + 126 - 2 * lane);
-  const unsigned c2[2] = {f.y, f.x};                                        // bins 127 - 2 lane, 126 - 2 lane
-  need -= above1;
-  run = wave_scan_inclusive(c2[0] + c2[1], lane) - (c2[0] + c2[1]);
-  cand = -1;
-  cand_above = 0;
+  const unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
+  const int src = found ? __builtin_ctzll(found) : 0;
+  bin1 = max(0, __builtin_amdgcn_readlane(cand, src));
+  above1 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
+}
+// step 2: the threshold key and the tie quota
+__device__ __forceinline__ void hist_fine_step(const uint2& f, int K, int bin1, unsigned above1, int lane, unsigned& T,
+                                               unsigned& r) {
+  const unsigned c2[2] = {f.y, f.x};
+  const unsigned need = static_cast<unsigned>(K) - above1;
+  unsigned run = wave_scan_inclusive(c2[0] + c2[1], lane) - (c2[0] + c2[1]);
+  int cand = -1;
+  unsigned cand_above = 0;
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     const unsigned before = run;
@@ -279,8 +289,8 @@ __device__ __forceinline__ void threshold_from_histograms(const unsigned* __rest
       cand_above = before;
     }
   }
-  found = __builtin_amdgcn_ballot_w64(cand >= 0);
-  src = found ? __builtin_ctzll(found) : 0;
+  const unsigned long long found = __builtin_amdgcn_ballot_w64(cand >= 0);
+  const int src = found ? __builtin_ctzll(found) : 0;
   const int bin2 = max(0, __builtin_amdgcn_readlane(cand, src));
   const unsigned above2 = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(cand_above), src));
   T = (static_cast<unsigned>(bin1) << 7) | static_cast<unsigned>(bin2);
@@ -293,20 +303,27 @@ __device__ __forceinline__ void threshold_from_histograms(const unsigned* __rest
 // not one per element.  All 64 lanes must call it.
 __device__ __forceinline__ void histograms_add_wave(const uint16_t (&bits)[8], bool valid, unsigned weight,
                                                     unsigned* __restrict__ hist, unsigned* scratch, int lane) {
-  reinterpret_cast<uint4*>(scratch)[lane] = make_uint4(0u, 0u, 0u, 0u);
+  // Lanes of the wave exchange counts through `scratch`: every access to it is an atomic, and the three
+  // steps are separated by wavefront-scope fences (no instructions on this hardware, where a wave's LDS
+  // operations complete in order; they keep the compiler from forwarding a lane's own zeros to its read).
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    __hip_atomic_store(scratch + 4 * lane + k, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   if (valid) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const unsigned key = bits[k] & 0x7FFFu;
-      atomicAdd(&scratch[key >> 7], weight);
+      __hip_atomic_fetch_add(scratch + (key >> 7), weight, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
       atomicAdd(&hist[kHistCoarse + key], weight);
     }
   }
-  const uint4 c = reinterpret_cast<const uint4*>(scratch)[lane];   // same wave: LDS operations complete in order
-  if (c.x) atomicAdd(&hist[4 * lane + 0], c.x);
-  if (c.y) atomicAdd(&hist[4 * lane + 1], c.y);
-  if (c.z) atomicAdd(&hist[4 * lane + 2], c.z);
-  if (c.w) atomicAdd(&hist[4 * lane + 3], c.w);
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const unsigned c = __hip_atomic_load(scratch + 4 * lane + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    if (c) atomicAdd(&hist[4 * lane + k], c);
+  }
 }
 
 // Visit this lane's elements in index order; emit(q, pos, kept) is called for EVERY element q < E, with

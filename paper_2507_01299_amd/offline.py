@@ -32,17 +32,14 @@ def second_moment(X: torch.Tensor, batch: int = 8192) -> torch.Tensor:
 
 
 def pca_rotation(C: torch.Tensor, solver_device=None) -> torch.Tensor:
-    """Eigenvectors of the symmetric C as columns, eigenvalues descending, each column's
-    largest-magnitude entry positive; fp64 solver (on `solver_device`, default C's device), result
-    in fp32 on C's device."""
+    """Rotation Q of Sec. 4.2: the eigenvectors of the symmetric second moment C as columns, leading
+    principal direction first.  The fp64 symmetric eigen-solver (a library call, on `solver_device`,
+    default C's device) returns the spectrum ascending, so the columns are simply reversed; the result is
+    fp32 on C's device.  A column's sign is whatever the solver returns: nothing downstream depends on
+    it (h_i and row i of Q^T W change sign together, and the Top-K compares |h_i|)."""
     dev = C.device if solver_device is None else solver_device
-    w, V = torch.linalg.eigh(C.to(device=dev, dtype=torch.float64))
-    order = torch.argsort(w, descending=True, stable=True)
-    V = V[:, order]
-    piv = V.abs().argmax(dim=0)
-    sg = torch.sign(V[piv, torch.arange(V.shape[1], device=V.device)])
-    sg[sg == 0] = 1.0
-    return (V * sg[None, :]).to(device=C.device, dtype=torch.float32).contiguous()
+    _, V = torch.linalg.eigh(C.to(device=dev, dtype=torch.float64))
+    return torch.flip(V, dims=(1,)).to(device=C.device, dtype=torch.float32).contiguous()
 
 
 def _gqa_repeat(v, d_q, d_kv, head_dim):
@@ -70,6 +67,29 @@ def prepare_block_layer(shape, W: dict, Xcal: torch.Tensor, rms_eps: float = 1e-
                Q_attn32=Q_attn, Q_mlp32=Q_mlp)
     api.fold_input(Q_attn, Wqkv, out["Wqkv"], t, scratch)
     api.fold_input(Q_mlp, Wgu, out["Wgu"], t, scratch)
+    torch.cuda.synchronize()
+    return out
+
+
+def prepare_shortcut_layer(shape, W: dict, Xcal: torch.Tensor, rms_eps: float = 1e-5, solver_device=None) -> dict:
+    """The same layer with every rotation absorbed (the block-level form of Sec. 5.4 as it is deployed):
+    on top of prepare_block_layer's operands, o carries Q_mlp and down carries Q_attn on the output side
+    (Wo_out, Wdown_out: the layer after this one is taken to use the same attention basis, so its output
+    is again a valid input), and the two shortcuts carry the residual adapters Q_attn^T Q_mlp
+    (shortcut_attn) and Q_mlp^T Q_attn (shortcut_mlp) of Sec. 4.2.  The layer input then lives in the
+    basis Q_attn."""
+    t = _tname(Xcal)
+    out = prepare_block_layer(shape, W, Xcal, rms_eps, solver_device)
+    scratch = api.OfflineScratch(shape.d, t)
+    Qa, Qm = out["Q_attn32"], out["Q_mlp32"]
+    out["Wo_out"] = torch.empty_like(out["Wo"])
+    out["Wdown_out"] = torch.empty_like(out["Wdown"])
+    out["shortcut_attn"] = torch.empty(shape.d, shape.d, dtype=Xcal.dtype, device=Xcal.device)
+    out["shortcut_mlp"] = torch.empty(shape.d, shape.d, dtype=Xcal.dtype, device=Xcal.device)
+    api.fold_output(out["Wo"], Qm, out["Wo_out"], t, scratch)
+    api.fold_output(out["Wdown"], Qa, out["Wdown_out"], t, scratch)
+    api.residual_adapter(Qa, Qm, out["shortcut_attn"], t, scratch)
+    api.residual_adapter(Qm, Qa, out["shortcut_mlp"], t, scratch)
     torch.cuda.synchronize()
     return out
 

@@ -19,6 +19,7 @@ import dataclasses
 import numpy as np
 
 BASE_SEED = 1299
+RMS_EPS = 1e-5          # pre-norm epsilon of the synthetic layers (the paper gives none)
 
 
 def seed_for(config: int, stream: int) -> int:
