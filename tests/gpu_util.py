@@ -27,6 +27,36 @@ def rel_l2(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.linalg.norm(got - want) / den) if den > 0 else float(np.linalg.norm(got))
 
 
+ULP_FRACTION = 0.02       # share of entries that may sit one unit in the last place off the oracle's rounding
+
+
+def _ordered(bits: np.ndarray) -> np.ndarray:
+    """16-bit patterns as integers that count representable values (sign-magnitude -> two's complement)."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b)
+
+
+def stored_close(got_bits: np.ndarray, want64: np.ndarray, dtype: str, what: str, tol=REL_L2_TOL) -> float:
+    """A stored 16-bit tensor against the oracle's value after the same single rounding: relative L2 within
+    `tol`, AND entry by entry at most one unit in the last place away, on at most ULP_FRACTION of the entries.
+    Entries whose absolute error is below 2^-16 of the tensor's rms are accepted whatever their ulp count: the
+    fp32 accumulation of a few thousand products is that uncertain, and for an entry that nearly cancels it is
+    more than the entry's own (tiny) ulp.  Returns the relative L2 error."""
+    want_bits = O.encode16(want64, dtype)
+    got, want = O.decode16(got_bits, dtype), O.decode16(want_bits, dtype)
+    e = rel_l2(got, want)
+    assert e <= tol, f"{what}: rel-L2 {e:.3e} > {tol:.1e}"
+    step = np.abs(_ordered(np.asarray(got_bits)) - _ordered(want_bits))
+    err = np.abs(got - want)
+    floor = 2.0 ** -16 * float(np.sqrt(np.mean(want * want))) if want.size else 0.0
+    bad = (step > 1) & (err > floor)
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {bad.size} entries beyond 1 ulp, worst {int(step[bad].max())} ulp, "
+                           f"abs err {err[bad].max():.3e} (floor {floor:.3e})")
+    frac = float(((step != 0) & (err > floor)).mean()) if step.size else 0.0
+    assert frac <= ULP_FRACTION, f"{what}: {frac:.4f} of the entries are one ulp off"
+    return e
+
+
 def device_layer(case, device="cuda:0"):
     from paper_2507_01299_amd import api
     L, b, dt = case.layer, case.bits, case.shape.dtype
@@ -43,7 +73,8 @@ def device_layer(case, device="cuda:0"):
 def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.Tensor, tol=REL_L2_TOL,
                       attn_bits: np.ndarray | None = None) -> dict:
     """Every stage of the GPU trace against the oracle applied to the GPU's own inputs of that
-    stage.  Index arrays must be equal; 16-bit tensors within tol relative L2.  Returns the
+    stage.  Index arrays must be equal; 16-bit tensors within tol relative L2 and, entry by entry, within
+    one unit in the last place on a bounded share of the entries (stored_close).  Returns the
     worst relative error per stage.  attn_bits: the output of a caller's attention core that was
     handed to the second half of a split layer run; h2 must then be exactly that."""
     dt = L.dtype
@@ -53,9 +84,8 @@ def check_layer_trace(L: O.Layer, x_bits: np.ndarray, trace: dict, x_out: torch.
     worst = {}
 
     def close(name, got_bits, want64):
-        e = rel_l2(O.decode16(got_bits, dt), want64)
+        e = stored_close(got_bits, want64, dt, name, tol)
         worst[name] = max(worst.get(name, 0.0), e)
-        assert e <= tol, f"{name}: rel-L2 {e:.3e} > {tol:.1e}"
 
     for b in range(B):
         x = O.decode16(x_bits[b], dt)

@@ -305,6 +305,30 @@ def test_config1_llama2_7b_shortcut_form_full_size(api):
     torch.cuda.synchronize()
     worst = check_layer_trace(L, xb, tr, out)
     print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    # the same layer at the kept counts of the paper's own allocation for this model (App. B table of optimal
+    # coefficients: alpha = 0.90 / 1.30 / 0.80 / 1.15 at 40 %; counts from tests/golden/appendix_b_kept_counts.txt)
+    Ks = _golden_counts("LLaMA2-7B", "0.40")
+    assert Ks == (2211, 3194, 1966, 7587)
+    L.K1, L.K2, L.K3, L.K4 = Ks
+    dl.c.K1, dl.c.K2, dl.c.K3, dl.c.K4 = Ks
+    ws = api.Workspace(dl.workspace_bytes(1))
+    tr = dl.trace_buffers(1)
+    print("running at the App. B counts", Ks, flush=True)
+    api.layer_forward(dl, x, out, ws, tr)
+    torch.cuda.synchronize()
+    assert tuple(tr[k].shape[1] for k in ("idx1", "idx2", "idx3", "idx4")) == Ks
+    worst = check_layer_trace(L, xb, tr, out)
+    print("worst rel-L2 per stage:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
+def _golden_counts(model, p):
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "appendix_b_kept_counts.txt")) as f:
+        for line in f:
+            t = line.split()
+            if t and t[0] == model and t[1] == p:
+                return tuple(int(v) for v in t[4:8])
+    raise KeyError((model, p))
 
 
 def test_config1_llama2_7b_layer_full_size(api):
@@ -321,14 +345,14 @@ def test_config1_llama2_7b_layer_full_size(api):
 
 
 def test_config2_llama3_8b_gqa_bf16_batched_sparsities(api):
-    """LLaMA3-8B-shaped layer (GQA, d_kv = 1024), bf16, decode batch 1 / 4 / 16 with independent
-    per-token index sets, sparsity 25 / 40 / 50 %."""
+    """LLaMA3-8B-shaped layer (GQA, d_kv = 1024), bf16: every cell of decode batch 1 / 4 / 16 (independent
+    per-token index sets) x sparsity 25 / 40 / 50 %, each stage of each token against the oracle."""
     shape = synth.SHAPES["llama3-8b"]
     print("building llama3-8b case", flush=True)
     case = cases.build_block_layer(shape, 0.4, seed=synth.seed_for(2, 0), n_cal=4096)
     L = case.layer
     dl = device_layer(case)
-    for p, B in ((0.25, 4), (0.40, 16), (0.50, 1)):
+    for p, B in [(p, B) for p in (0.25, 0.40, 0.50) for B in (1, 4, 16)]:
         Ks = (O.kept_count(shape.d, p), O.kept_count(shape.d_q, p), O.kept_count(shape.d, p),
               O.kept_count(shape.d_ff, p))
         assert Ks in ((3072, 3072, 3072, 10752), (2457, 2457, 2457, 8601), (2048, 2048, 2048, 7168))
@@ -393,22 +417,81 @@ def test_config3_llama2_70b_shortcut_form_full_size(api):
 
 def test_config4_folded_stack_llama2_7b_shape(api):
     """Deployed form at LLaMA2-7B layer shape: rotations folded (no explicit Q), per-layer adapter as
-    a dense 4096 x 4096 mat-vec; a 2-layer slice of the stack, batch 8, every stage of every layer
-    checked.  (The full 32-layer stack differs only in the number of such layers.)"""
+    a dense 4096 x 4096 mat-vec; a 2-layer slice of the stack at batch 1, 8 and 32 (32 tokens fill the
+    matrix-core kernel's two-tile token group), every stage of every layer and token checked.
+    (The full 32-layer stack differs only in the number of such layers.)"""
     shape = synth.SHAPES["llama2-7b"]
     print("building 2 folded llama2-7b layers", flush=True)
     layers, bits, Qs, Ws, src = cases.build_folded_stack(shape, 2, 0.4, seed=synth.seed_for(4, 0), n_cal=4096)
-    B = 8
-    x0 = O.rotate(src.draw(B, seed=synth.seed_for(4, 5)), Qs[0])
-    cur = to_dev(O.encode16(x0, shape.dtype), shape.dtype)
-    for li, (L, b) in enumerate(zip(layers, bits)):
+    dls = [device_layer(cases.LayerCase(shape, b, L, {}, src)) for L, b in zip(layers, bits)]
+    for B in (1, 8, 32):
+        x0 = O.rotate(src.draw(B, seed=synth.seed_for(4, 5) + B), Qs[0])
+        cur = to_dev(O.encode16(x0, shape.dtype), shape.dtype)
+        for li, (L, dl) in enumerate(zip(layers, dls)):
+            print(f"batch {B} layer {li}", flush=True)
+            ws = api.Workspace(dl.workspace_bytes(B))
+            out = torch.zeros_like(cur)
+            tr = dl.trace_buffers(B)
+            api.layer_forward(dl, cur, out, ws, tr)
+            torch.cuda.synchronize()
+            check_layer_trace(L, to_bits(cur), tr, out)
+            cur = out
+            del ws, tr
+
+
+def test_config4_chain_of_layers_in_the_benchmarked_graph_form(api):
+    """The form `bench.py --config 4` times: one rotation Q_l per layer, every rotation absorbed (q|k|v and
+    gate|up carry Q_l^T, o carries Q_l, down carries Q_{l+1}), the residual adapter Q_l^T Q_{l+1} on the MLP
+    shortcut only, at the LLaMA2-7B layer shape, batch 1.  A chain of 4 such layers, each layer's every stage
+    checked against the oracle on the GPU's own input of that layer; then the same chain as ONE HIP graph,
+    replayed with eager work in between, must reproduce the eager chain's output bits every time.
+    The bases are seeded orthogonal matrices (any orthogonal matrices give a valid layer), so the host
+    pays for the fp64 folds only."""
+    shape = synth.SHAPES["llama2-7b"]
+    n = 4
+    seed = synth.seed_for(4, 0)
+    Qs = [synth.planted_basis(shape.d, seed + 11 * l) for l in range(n)]
+    print("building a 4-layer chain (fp64 folds on the host)", flush=True)
+    layers, bits, Qa, Ws, src = cases.build_shortcut_stack(shape, n, 0.4, seed=seed, n_cal=0, bases=(Qs, Qs))
+    for L, b in zip(layers, bits):      # Qa_l = Qm_l: the attention shortcut's adapter is the identity and is left out
+        L.shortcut_attn = None
+        b["shortcut_attn"] = None
+    dls = [device_layer(cases.LayerCase(shape, b, L, {}, src)) for L, b in zip(layers, bits)]
+    ws = api.Workspace(max(dl.workspace_bytes(1) for dl in dls))
+    x0 = to_dev(O.encode16(O.rotate(src.draw(1, seed=synth.seed_for(4, 5)), Qs[0]), shape.dtype), shape.dtype)
+    cur = x0
+    outs = []
+    for li, (L, dl) in enumerate(zip(layers, dls)):
         print(f"layer {li}", flush=True)
-        dl = device_layer(cases.LayerCase(shape, b, L, {}, src))
-        ws = api.Workspace(dl.workspace_bytes(B))
         out = torch.zeros_like(cur)
-        tr = dl.trace_buffers(B)
+        tr = dl.trace_buffers(1)
         api.layer_forward(dl, cur, out, ws, tr)
         torch.cuda.synchronize()
         check_layer_trace(L, to_bits(cur), tr, out)
+        outs.append(out)
         cur = out
-        del dl, ws, tr
+    final_bits = to_bits(cur)
+    # the chain as one graph (no trace buffers), as the bench builds it
+    bufs = [torch.zeros_like(x0), torch.zeros_like(x0)]
+
+    def chain():
+        c = x0
+        for i, dl in enumerate(dls):
+            api.layer_forward(dl, c, bufs[i & 1], ws)
+            c = bufs[i & 1]
+
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        chain()
+    for rep in range(3):
+        bufs[0].zero_(); bufs[1].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(bufs[(n - 1) & 1]), final_bits), f"graph replay {rep}"

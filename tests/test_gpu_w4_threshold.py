@@ -7,7 +7,7 @@ import torch
 
 from oracle import larosa_oracle as O
 from paper_2507_01299_amd import synth
-from tests.gpu_util import REL_L2_TOL, rel_l2, to_bits, to_dev
+from tests.gpu_util import REL_L2_TOL, rel_l2, stored_close, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -109,6 +109,46 @@ def test_w4_projection_full_size_gate_up(api, ws, w4_geometry):
     torch.cuda.synchronize()
     want = O.round16(O.sparse_project_w4(h[0], idx[0], codes, sbits, dtype), dtype)
     assert rel_l2(O.decode16(to_bits(y), dtype)[0], want) <= REL_L2_TOL
+
+
+def test_w4_wide_geometry_at_the_shape_that_selects_it(api):
+    """gate|up of the LLaMA2-70B-shaped layer: 8192 x 57344, K = 4915 (40 % sparsity), bf16 -- the one
+    benchmark shape whose output is wide enough for the 2048-column geometry to be chosen by the library
+    itself (no tuning override).  Weights are drawn and quantised on the device (the quantiser is checked
+    bit for bit above, and again here on sampled rows); the projection is checked on sampled output
+    columns that span several strips, the ragged last one included, against the oracle's product over
+    the same codes and scales."""
+    dtype, d_in, d_out, K = "bf16", 8192, 57344, 4915
+    print("sparse_gemv_w4 8192 x 57344, default geometry", flush=True)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1299)
+    Wd = (torch.randn(d_in, d_out, generator=gen, device="cuda:0", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    Wq, sc = api.quantize_w4(Wd, dtype)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(91)
+    rows = np.sort(rng.choice(d_in, 8, replace=False))
+    c_or, s_or = O.quantize_rtn_w4(O.decode16(to_bits(Wd[torch.from_numpy(rows).cuda()]), dtype), dtype)
+    codes_rows = O.unpack_w4(Wq[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint32))
+    assert np.array_equal(codes_rows, c_or) and np.array_equal(to_bits(sc[torch.from_numpy(rows).cuda()]), s_or)
+    del Wd
+    hb, h = _heavy(rng, 1, d_in, dtype)
+    idx = O.topk_batch(hb, K)
+    ws = api.workspace(1, d_in, d_out, K)
+    y = torch.zeros(1, d_out, dtype=torch.bfloat16, device="cuda:0")
+    api.sparse_gemv_w4(Wq, sc, to_dev(hb, dtype), torch.from_numpy(idx).cuda(), y, dtype, ws)
+    torch.cuda.synchronize()
+    # sampled groups of 128 columns (one scale group each): first, last, strip boundaries, random ones
+    groups = sorted({0, 15, 16, 17, d_out // 128 - 1, *rng.choice(d_out // 128, 12, replace=False).tolist()})
+    kept = torch.from_numpy(idx[0].astype(np.int64)).cuda()
+    Wq_k, sc_k = Wq[kept], sc[kept]                 # the kept rows' codes and scales
+    got = O.decode16(to_bits(y), dtype)[0]
+    for gidx in groups:
+        c0 = gidx * 128
+        codes_g = O.unpack_w4(Wq_k[:, c0 // 8:(c0 + 128) // 8].contiguous().cpu().numpy().view(np.uint32))   # [K, 128]
+        sb_g = to_bits(sc_k[:, gidx:gidx + 1].contiguous())                                                  # [K, 1]
+        want = O.round16(O.sparse_project_w4(h[0][idx[0]], np.arange(K), codes_g, sb_g, dtype), dtype)
+        stored_close(to_bits(y)[0][c0:c0 + 128], want, dtype, f"columns {c0}..{c0 + 127}")
+    assert np.isfinite(got).all()
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
