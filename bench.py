@@ -433,6 +433,9 @@ def main():
     ap.add_argument("--threshold-comparator", action="store_true",
                     help="per-token time and kept-count spread of the magnitude-threshold sparsifier against "
                          "Top-K on a synthetic token stream with scale drift; prints its own JSON line")
+    ap.add_argument("--host-solver", action="store_true",
+                    help="run the eigen-solver of the weight preparation on the host (the device solver does not "
+                         "run under hardware-counter collection)")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="larosa_set_tuning(KEY, VALUE) before anything is sized (experiments)")
     args = ap.parse_args()
@@ -482,7 +485,7 @@ def main():
     Wdev = {k: torch.as_tensor(v).to(dev).to(td).contiguous() for k, v in W.items()}
     Xcd = torch.as_tensor(Xc).to(dev).to(td).contiguous()
     ops0 = offline.prepare_shortcut_layer(shape, Wdev, Xcd, rms_eps=synth.RMS_EPS,
-                                          solver_device="cpu" if d > 4096 else None)
+                                          solver_device="cpu" if (d > 4096 or args.host_solver) else None)
     del W, Xc, Wdev, Xcd
     x = torch.as_tensor(src.draw(B, synth.seed_for(args.config, 5))).to(dev).to(td).contiguous()
     x_explicit = x

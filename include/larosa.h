@@ -20,11 +20,16 @@
  *  - Scratch memory comes from the caller's workspace `ws` (256-byte aligned) of at least
  *    the number of bytes the matching *_workspace_bytes() query returns.  A workspace must
  *    be passed once through larosa_workspace_init() after allocation (it zeroes the
- *    arrival counters; the kernels leave them zero again on exit).  Two calls that use the
- *    same workspace must be ordered on one stream.
+ *    arrival counters at its head; the kernels leave them zero again on exit).
+ *    One workspace serves one stream: two calls that use the same workspace must be ordered on
+ *    one stream (calls that overlap on one workspace corrupt each other's partial sums and
+ *    counters, silently).
  *  - Return value: LAROSA_OK (0) or a negative larosa_status.  Invalid arguments are
  *    rejected before anything is enqueued.  LAROSA_EHIP reports a failed launch
- *    (hipGetLastError() != hipSuccess after enqueueing).
+ *    (hipGetLastError() != hipSuccess after enqueueing).  After LAROSA_EHIP -- or after any
+ *    launch that was aborted or faulted -- the arrival counters of the workspace may be left
+ *    non-zero: pass it through larosa_workspace_init() again before the next call.
+ *  - Index values (idx) are not range-checked: an index outside [0, d_in) reads outside Wp.
  */
 #ifndef LAROSA_H
 #define LAROSA_H
@@ -81,7 +86,8 @@ int larosa_dense_gemv(const void* Wp, const void* x, void* y, int B, int d_in, i
  * unsigned integer); ties go to the larger magnitude, then to the lower index; exactly K
  * indices are produced, in ascending order.
  * h [B,d]; idx [B,K] int32 (output); vals [B,K] (output, nullable) receives h[b, idx[b,t]].
- * 1 <= K <= d <= 32768. */
+ * 1 <= K <= d <= 32768.  ws / ws_bytes are not used (the selection needs no scratch in device
+ * memory; the arguments keep the signature uniform) and may be NULL / 0. */
 int larosa_topk(const void* h, int B, int d, int K, int32_t* idx, void* vals,
                 larosa_dtype t, void* ws, size_t ws_bytes, void* stream);
 
@@ -250,16 +256,21 @@ int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, con
 int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype t, int32_t* idx, int32_t* count,
                             void* stream);
 
-/* Kernel launch tuning for experiments (host state, not thread-safe; set it before sizing a
- * workspace): key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
- * key 1 = minimum (strip, row) pairs per workgroup, key 2 = row-waves per workgroup (0: 8, 1: 16,
- * 2: 4), key 3 = decoder layer with the Top-K fused into the projection kernels (1, default) or
- * as separate kernels (0), key 4 = row-waves per workgroup of that fused kernel (8 or 16),
+/* ---- NOT part of the stable interface: launch tuning for tests and experiments.
+ * Process-wide host state read by every call (launch shapes AND workspace sizes depend on it): not
+ * thread-safe; change it only while no call of this library is in flight, and before sizing a workspace.
+ * Production callers never call it: the defaults are derived from the arguments of each call.
+ * key 0 = target number of workgroups of the row-streaming kernels (0 = automatic),
+ * key 1 = minimum kept rows per workgroup, key 2 = row-waves per workgroup of the stand-alone
+ * row-streaming kernel (0: 8, 1: 16, 2: 4), key 3 = decoder layer with the Top-K fused into the
+ * projection kernels (1, default) or as separate kernels (0),
  * key 5 / key 6 = workgroups of a projection / of the shortcut adapter that shares its launch
  * (0 = chosen from the two jobs' sizes, default),
  * key 7 = narrowest output width for which the 4-bit projection uses its 2048-column geometry,
- * key 8 = widest MLP intermediate vector whose Top-K runs inside the down projection's workgroups
- * (wider ones are selected once by the Top-K kernel).
+ * key 8 = with key 9 = 0: widest MLP intermediate vector whose Top-K runs inside the down projection's
+ * workgroups (wider ones are selected once by the Top-K kernel),
+ * key 9 = batch-1 decoder layer: the down projection takes its Top-K threshold from key histograms
+ * that the gate|up launch builds (1, default) or selects for itself (0).
  * Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 

@@ -47,5 +47,20 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_diag(verbose: bool = False) -> str:
+    """Compile the diagnostic program csrc/diag_phase_clock.hip (the projection kernels with their phase
+    clocks compiled in, plus a small driver) into _build/diag_phase_clock.  Not needed by the library."""
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    exe = os.path.join(objdir, "diag_phase_clock")
+    cmd = [hipcc()] + [f for f in FLAGS if f not in ("-shared", "-fPIC")] + [os.path.join(CSRC, "diag_phase_clock.hip"),
+                                                                             "-o", exe]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, cwd=CSRC)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    print(build_diag(verbose=True) if "--diag" in sys.argv[1:] else build_library(verbose=True))

@@ -920,10 +920,6 @@ int larosa_set_tuning(int key, int value) {
       if (value < 0 || value > 1) return LAROSA_EINVAL;
       tuning().fused = value;
       return LAROSA_OK;
-    case 4:
-      if (value != 8 && value != 16) return LAROSA_EINVAL;
-      tuning().fused_rw = value;
-      return LAROSA_OK;
     case 5:
       if (value != 0 && (value < 8 || value > 2048)) return LAROSA_EINVAL;
       tuning().side_main_g = value;

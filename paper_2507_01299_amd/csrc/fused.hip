@@ -374,10 +374,8 @@ hipError_t launch_nv(const FusedArgs& a, hipStream_t st) {
   LAROSA_FUSED_CASE(4)
   LAROSA_FUSED_CASE(6)
   LAROSA_FUSED_CASE(8)
-  if (RW == 8) {
-    LAROSA_FUSED_CASE(12)
-    LAROSA_FUSED_CASE(16)
-  }
+  LAROSA_FUSED_CASE(12)
+  LAROSA_FUSED_CASE(16)
 #undef LAROSA_FUSED_CASE
   return hipErrorInvalidValue;
 }
@@ -400,18 +398,14 @@ hipError_t launch_hinted(const FusedArgs& a, hipStream_t st) {
 template <typename T>
 hipError_t launch_rw(const FusedArgs& a, hipStream_t st) {
   if (a.hist_in) return launch_hinted<T>(a, st);
-  return fused_row_waves() == 16 ? launch_nv<T, 16>(a, st) : launch_nv<T, 8>(a, st);
+  return launch_nv<T, 8>(a, st);
 }
 
 }  // namespace
 
-int fused_row_waves() { return tuning().fused_rw == 16 ? 16 : 8; }
-
 GemvPlan plan_fused(int d_out, int K, int g_hint, int pair_cols) {
   // paired strips: ceil(d_ff / 256) strips of 512 columns (256 gate + 256 up); plan_gemv only needs the count
   const int cols = pair_cols > 0 ? (pair_cols + 255) / 256 * kStripCols : d_out;
-  if (fused_row_waves() == 16 && tuning().g_target == 0 && g_hint == 0)
-    g_hint = 256;   // 1024-lane workgroups: one per compute unit, so the redundant prologue runs once per CU
   return plan_gemv(cols, K, g_hint, kStripCols, kFusedChunkMax);
 }
 

@@ -381,8 +381,6 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[NA], int s, int b
   }
 }
 
-constexpr int kRowListMax = 2048;   // ranks of a workgroup whose rows are staged in LDS
-
 // Copy the (row, coefficient) pairs of the ranks [t0, t0 + count) into LDS (entry e = rank t0 + e).
 // Returns false (and copies nothing) when the list does not fit; ends with a barrier otherwise.
 // Uniform over the workgroup.

@@ -41,7 +41,6 @@ struct Tuning {
   int min_rows = 8;           // minimum row-strips per workgroup
   int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
-  int fused_rw = 8;           // row-waves of the fused kernel: 8 (two workgroups per CU) or 16 (one)
   int side_main_g = 0;        // workgroups of a projection that shares its launch with a shortcut adapter; 0 = by size
   int w4_wide_min_cols = 32768;   // 4-bit kernel: narrowest output that uses the 2048-column geometry
   int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
@@ -51,8 +50,9 @@ struct Tuning {
 Tuning& tuning();
 
 // g_hint > 0 asks for that many workgroups instead of the automatic choice
-// max_ranks > 0 caps the ranks per workgroup (more workgroups per strip instead)
-GemvPlan plan_gemv(int d_out, int K, int g_hint = 0, int strip_cols = 512, int max_ranks = 0);
+constexpr int kRowListMax = 2048;   // ranks of a workgroup whose (row, coefficient) pairs are staged in LDS
+// max_ranks caps the ranks per workgroup (more workgroups per strip instead), so that its list fits in LDS
+GemvPlan plan_gemv(int d_out, int K, int g_hint = 0, int strip_cols = 512, int max_ranks = kRowListMax);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
 
 // The same mat-vec over 4-bit weights (w4.hip): g.W is unused; the row loop reads packed codes and
@@ -109,7 +109,6 @@ constexpr int kHistWords = kHistCoarse + 32768;
 constexpr int kHintMaxWidth = 32768;   // widest input vector of the launch form that takes hist_in
 // pair_cols > 0: strips are 256 channels of gate and of up each (see FusedArgs)
 GemvPlan plan_fused(int d_out, int K, int g_hint = 0, int pair_cols = 0);
-int fused_row_waves();
 hipError_t launch_fused(const FusedArgs& a, bool bf16, hipStream_t s);
 
 // Batched variant: y[b,:] = epilogue( sum_j C[b,j] * W[j,:] ) over ALL rows j, where C holds each

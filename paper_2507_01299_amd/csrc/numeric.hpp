@@ -3,6 +3,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// The kernels rely on gfx950 behaviour that the HIP memory model does not promise (see the hand-off in
+// gemv_core.hpp): accesses with the sc1 cache policy are coherent across the chip's eight L2 slices, a
+// wave's s_waitcnt vmcnt(0) returns only after its stores were acknowledged there, and wave64 DPP /
+// MFMA forms of this target.  Refuse to build the device code for anything else.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "liblarosa's device code is written for gfx950 (MI355X) only"
+#endif
+
 // Phase clocks of a diagnostic build (-DLAROSA_PHASE_CLOCK): lane 0 of a workgroup stores the
 // 100 MHz wall clock to slot `n` of its row in a buffer whose address the host puts into
 // larosa_phase_clock (null: off).  Product builds compile the stamps to nothing.

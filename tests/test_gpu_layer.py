@@ -32,15 +32,16 @@ def _run_layer(api, case, B, seed, trace=True):
     return xb, out, tr, dl, ws
 
 
-@pytest.fixture(params=[(1, 8), (1, 16), (0, 8)], ids=["fused8", "fused16", "separate"])
+@pytest.fixture(params=[(1, 1), (1, 0), (0, 1)], ids=["fused", "fused-no-histograms", "separate"])
 def fused_mode(api, request):
-    """Run the layer with the Top-K fused into the projection kernels (512- and 1024-lane
-    workgroups) and as separate kernels."""
+    """Run the layer with the Top-K fused into the projection kernels -- with the down projection taking its
+    threshold from the histograms the gate|up launch builds, and with every launch selecting for itself --
+    and with the Top-K as separate kernels."""
     api.set_tuning(3, request.param[0])
-    api.set_tuning(4, request.param[1])
+    api.set_tuning(9, request.param[1])
     yield request.param
     api.set_tuning(3, 1)
-    api.set_tuning(4, 8)
+    api.set_tuning(9, 1)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
