@@ -54,7 +54,16 @@ size_t batched_partial_bytes(const GemvPlan& p, int B, bool coef_scale) {
 int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st, BatchArgs side = BatchArgs{}) {
   const bool cs = a.coef_scale != nullptr;
   const bool has_side = side.W != nullptr && batched_uses_mfma(a.B, cs);
-  const GemvPlan p = plan_batched(a.d_in, a.d_out, batched_uses_mfma(a.B, cs));
+  // two products in one launch share the chip in proportion to the bytes each has to read
+  int g_main = 0, g_side = 0;
+  if (has_side) {
+    const double bm = static_cast<double>(a.d_in) * a.d_out, bs = static_cast<double>(side.d_in) * side.d_out;
+    const int total = batched_g_total();
+    g_side = static_cast<int>(total * bs / (bm + bs) + 0.5);
+    if (g_side < 1) g_side = 1;
+    g_main = total - g_side > 0 ? total - g_side : 1;
+  }
+  const GemvPlan p = plan_batched(a.d_in, a.d_out, batched_uses_mfma(a.B, cs), g_main);
   const int tpg = batched_tokens_per_group(a.B, cs);
   const size_t groups = (a.B + tpg - 1) / tpg;
   size_t slots = groups * p.nstrips;
@@ -63,7 +72,7 @@ int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t s
   char* partial = static_cast<char*>(ws) + kCounterBytes;
   BatchPair pr{};
   if (has_side) {
-    const GemvPlan ps = plan_batched(side.d_in, side.d_out, true);
+    const GemvPlan ps = plan_batched(side.d_in, side.d_out, true, g_side);
     side.chunk = ps.chunk;
     side.G = ps.G;
     side.nstrips = ps.nstrips;
@@ -495,7 +504,7 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
   mark(0);
   if (B > 1) {
     // Batched decode: per-token Top-K writes each token's activations with the dropped channels
-    // zeroed, and one pass over all weight rows serves every token (the union of the index sets).
+    // zeroed (the index lists only when the caller traces them: the products do not read them), and one pass over all weight rows serves every token (the union of the index sets).
     // a projection over the masked activations; the shortcut adapter of the block (scA: dst = src scA)
     // shares its launch
     auto project = [&](const void* W, int d_in, int d_out, uint16_t* y, const uint16_t* residual, uint16_t* y_pre,
@@ -529,7 +538,7 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
       return launch_topk_from(sc, B, d, K, idx, masked, bf, st) == hipSuccess ? LAROSA_OK : LAROSA_EHIP;
     };
     if (part != kAfterAttention) {
-      LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, idx1, 1));
+      LAROSA_TRY(input_and_select(x, L->Q_attn, L->rms_attn, h1, L->K1, T.idx1, 1));
       LAROSA_TRY(project(L->Wqkv, d, d_qkv, qkv, nullptr, nullptr, s1 ? L->shortcut_attn : nullptr, x, s1));
       mark(2);
       if (part == kUntilQkv) return LAROSA_OK;
@@ -539,17 +548,17 @@ int layer_run(const larosa_layer* L, const void* x_in, void* x_out, int B, const
       sc.mode = attn ? kSrcPlain : kSrcGqa; sc.src = attn ? attn : qkv; sc.h_out = h2;
       sc.d_q = d_q; sc.d_kv = d_kv; sc.head_dim = L->head_dim;
       sc.group = (d_q / L->head_dim) / (d_kv / L->head_dim);
-      LAROSA_HIP(launch_topk_from(sc, B, d_q, L->K2, idx2, masked, bf, st));
+      LAROSA_HIP(launch_topk_from(sc, B, d_q, L->K2, T.idx2, masked, bf, st));
     }
     LAROSA_TRY(project(L->Wo, d_q, d, x1, s1 ? s1 : x, o));
     mark(3);
-    LAROSA_TRY(input_and_select(x1, L->Q_mlp, L->rms_mlp, h3, L->K3, idx3, 4));
+    LAROSA_TRY(input_and_select(x1, L->Q_mlp, L->rms_mlp, h3, L->K3, T.idx3, 4));
     LAROSA_TRY(project(L->Wgu, d, 2 * d_ff, gu, nullptr, nullptr, L->shortcut_mlp, x1, s2));
     mark(5);
     {
       TopkSource sc{};
       sc.mode = kSrcSilu; sc.src = gu; sc.h_out = h4;
-      LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, idx4, masked, bf, st));
+      LAROSA_HIP(launch_topk_from(sc, B, d_ff, L->K4, T.idx4, masked, bf, st));
     }
     LAROSA_TRY(project(L->Wdown, d_ff, d, x2, s2 ? s2 : x1, down));
     mark(6);

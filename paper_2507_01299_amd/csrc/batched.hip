@@ -335,6 +335,7 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
   const int K = a.d_in;
   const int chunk = a.chunk;
 
+  LAROSA_STAMP(0);
   int f0 = g * chunk;
   const int f1 = min(f0 + chunk, a.nstrips * K);
   int s = f0 / K;
@@ -408,6 +409,7 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
       }
     }
 
+    LAROSA_STAMP(1);
     const int n_s = ge.g_last - ge.g_first + 1;
     const size_t slot_floats = static_cast<size_t>(NTB) * 16 * kMStrip;
     unsigned long long* slot = reinterpret_cast<unsigned long long*>(
@@ -492,11 +494,13 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
+      LAROSA_STAMP(2);
       if (tid == 0) {
         const unsigned old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (old == static_cast<unsigned>(n_s - 1)) ? 1 : 0;
       }
       __syncthreads();
+      LAROSA_STAMP(3);
       if (s_last != 0) {   // uniform over the workgroup
         if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         token_scales<T, kMRW>(a, b0, NTB * 16, scale_s, lane, rw);
@@ -538,6 +542,7 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
     t0 = 0;
     seg_no += 1;
   }
+  LAROSA_STAMP(5);
 }
 
 
@@ -579,17 +584,19 @@ hipError_t launch_batched_t(const BatchPair& p, hipStream_t st) {
 
 bool batched_uses_mfma(int B, bool coef_scale) { return B >= 2 && !coef_scale; }
 
+int batched_g_total() { return tuning().g_target > 0 ? tuning().g_target : 256; }
+
 int batched_tokens_per_group(int B, bool coef_scale) {
   if (batched_uses_mfma(B, coef_scale)) return B <= 16 ? 16 : 32;
   return B <= 2 ? 2 : 4;
 }
 
-GemvPlan plan_batched(int d_in, int d_out, bool mfma) {
+GemvPlan plan_batched(int d_in, int d_out, bool mfma, int g_hint) {
   GemvPlan p;
   p.strip_cols = 128;   // both batched kernels work on 128-column strips
   p.nstrips = (d_out + p.strip_cols - 1) / p.strip_cols;
   const long T = static_cast<long>(p.nstrips) * d_in;
-  long G = tuning().g_target > 0 ? tuning().g_target : 256;     // one workgroup per compute unit
+  long G = g_hint > 0 ? g_hint : batched_g_total();             // one workgroup per compute unit
   if (G < p.nstrips) G = p.nstrips;
   long chunk = (T + G - 1) / G;
   chunk = (chunk + 15) / 16 * 16;                                // whole 16-row tiles; keeps row starts 8-aligned

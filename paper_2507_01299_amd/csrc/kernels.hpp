@@ -128,7 +128,9 @@ struct BatchArgs {
   uint16_t* y_pre;
 };
 constexpr int kBatchChunkMax = 4096;   // rows per workgroup segment (LDS coefficient staging)
-GemvPlan plan_batched(int d_in, int d_out, bool mfma);
+// g_hint > 0: number of workgroups to aim for (a product that shares its launch takes its share of the chip)
+GemvPlan plan_batched(int d_in, int d_out, bool mfma, int g_hint = 0);
+int batched_g_total();      // workgroups a whole batched launch aims for
 bool batched_uses_mfma(int B, bool coef_scale);
 int batched_tokens_per_group(int B, bool coef_scale);
 hipError_t launch_batched(const BatchArgs& a, bool bf16, hipStream_t s);

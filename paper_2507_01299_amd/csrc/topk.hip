@@ -7,6 +7,9 @@ namespace larosa {
 
 namespace {
 
+#ifndef LAROSA_TOPK_KERNEL_COPIES
+#define LAROSA_TOPK_KERNEL_COPIES kTopkCopiesWide
+#endif
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
 
@@ -18,11 +21,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
                                                             int32_t* __restrict__ idx,
                                                             uint16_t* __restrict__ vals,
                                                             uint16_t* __restrict__ masked, TopkSource sc) {
-  __shared__ TopkShared<kTopkWaves> sm;
+  __shared__ TopkShared<kTopkWaves, LAROSA_TOPK_KERNEL_COPIES> sm;
   const int b = blockIdx.x;
   const uint16_t* hb = h + static_cast<size_t>(b) * d;
   const int base = threadIdx.x * E;
 
+  LAROSA_STAMP(0);
   topk_clear<kTopkWaves>(sm);             // made visible by the first barrier below
   // All of the lane's loads are issued first, unconditionally and from addresses clamped into the
   // vector (d % 4 == 0: a group of four is all valid or all past the end; groups past the end re-read
@@ -122,20 +126,23 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
     }
   }
   if (sc.mode != kSrcNorm) __syncthreads();
+  LAROSA_STAMP(1);
   const auto st = block_select<kTopkWaves, E>(raw, K, sm);
+  LAROSA_STAMP(2);
 
-  int32_t* idxb = idx + static_cast<size_t>(b) * K;
+  int32_t* idxb = idx ? idx + static_cast<size_t>(b) * K : nullptr;   // the index list is optional
   uint16_t* valb = vals ? vals + static_cast<size_t>(b) * K : nullptr;
   uint16_t mk[E];
 #pragma unroll
   for (int q = 0; q < E; ++q) mk[q] = 0;
   for_each_kept<E>(st, [&](int q, unsigned pos, bool kept) {
     if (kept) {
-      idxb[pos] = base + q;
+      if (idxb) idxb[pos] = base + q;
       if (valb) valb[pos] = raw[q];
     }
     mk[q] = kept ? raw[q] : static_cast<uint16_t>(0);
   });
+  LAROSA_STAMP(3);
   if (masked) {
     uint16_t* mb = masked + static_cast<size_t>(b) * d;
 #pragma unroll
@@ -149,6 +156,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const uint16_t* __re
       }
     }
   }
+  LAROSA_STAMP(4);
 }
 
 // Magnitude-threshold sparsifier (Eq. 4-5), the comparison method with a data-dependent kept count:

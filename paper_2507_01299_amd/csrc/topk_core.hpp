@@ -38,10 +38,25 @@ constexpr bool kTopkAllWavesScan1 = LAROSA_TOPK_ALL_WAVES_SCAN1 != 0;
 constexpr int kTopkCopyStride = 260;   // words between copies: 16-byte aligned, and the copies of one bin fall in different LDS banks
 constexpr int kTopkCopyStride2 = 132;  // the same for the 128-bin pass (one copy per wave)
 
-template <int NW>
+// A workgroup that selects for a wide vector, or for bfloat16 (whose top 8 key bits are the exponent alone,
+// so nearly every lane of a wave adds to the same few bins), is bound by those same-word additions: with
+// kTopkCopiesWide copies (lane mod 32 picks the copy; stride 1 mod 32, so the 32 copies of one bin lie
+// in 32 different banks) at most two lanes of a wave ever meet in a word.  The copies are then summed by
+// the whole workgroup (one more barrier) before wave 0 walks the bins.
+constexpr int kTopkCopiesWide = 32;
+constexpr int kTopkCopyStrideWide = 257;
+// words of the pass-1 histograms, padded to a multiple of 4 (they are cleared in 16-byte pieces)
+template <int C> struct TopkHist1 { static constexpr int words = kTopkCopyStride * C; static constexpr int stride = kTopkCopyStride; };
+template <> struct TopkHist1<kTopkCopiesWide> {
+  static constexpr int words = (kTopkCopyStrideWide * kTopkCopiesWide + 3) / 4 * 4;
+  static constexpr int stride = kTopkCopyStrideWide;
+};
+
+template <int NW, int C = kTopkCopies>
 struct TopkShared {
-  alignas(16) unsigned hist[kTopkCopyStride * kTopkCopies];   // pass 1: word copy * kTopkCopyStride + bin
+  alignas(16) unsigned hist[TopkHist1<C>::words];             // pass 1: word copy * stride + bin
   unsigned hist2[kTopkCopyStride2 * NW];                      // pass 2: word wave * kTopkCopyStride2 + bin (adjacent: cleared in one step)
+  alignas(16) unsigned part[C == kTopkCopiesWide ? 256 * (NW / 4) : 4];   // wide copies: sums over NW/4 groups of copies
   unsigned wave_tot[NW];                                      // per wave: elements in bins above the threshold bin
   int bin;                                                    // pass-1 bin holding the K-th largest key, and the
   unsigned above;                                             // count strictly above it (written by wave 0)
@@ -75,12 +90,12 @@ struct TopkLaneT {
 
 // Zero both histograms; every lane of the workgroup calls it.  No barrier: the caller's next barrier
 // (it usually has one of its own while it builds the vector) makes the zeros visible.
-template <int NW>
-__device__ __forceinline__ void topk_clear(TopkShared<NW>& sm) {
-  constexpr int kWords = kTopkCopyStride * kTopkCopies + kTopkCopyStride2 * NW;   // hist and hist2 are adjacent
-  static_assert(offsetof(TopkShared<NW>, hist2) == sizeof(unsigned) * kTopkCopyStride * kTopkCopies,
-                "histograms must be adjacent");
-  static_assert(offsetof(TopkShared<NW>, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
+template <int NW, int C>
+__device__ __forceinline__ void topk_clear(TopkShared<NW, C>& sm) {
+  constexpr int kWords = TopkHist1<C>::words + kTopkCopyStride2 * NW;   // hist and hist2 are adjacent
+  typedef TopkShared<NW, C> Sh;
+  static_assert(offsetof(Sh, hist2) == sizeof(unsigned) * TopkHist1<C>::words, "histograms must be adjacent");
+  static_assert(offsetof(Sh, hist) % 16 == 0 && kWords % 4 == 0, "cleared and read in 16-byte pieces");
   uint4* flat = reinterpret_cast<uint4*>(sm.hist);
   for (int i = threadIdx.x; i < kWords / 4; i += NW * 64) flat[i] = make_uint4(0u, 0u, 0u, 0u);
 }
@@ -96,30 +111,50 @@ __device__ __forceinline__ unsigned wave_total(unsigned v, int lane) {
 // their number), so it is never kept -- and the passes over the elements need no per-element predicate.
 // Every lane of the NW-wave workgroup must call this, after topk_clear and a workgroup barrier.
 // 1 <= K <= total number of valid elements <= 32768.
-template <int NW, int E>
+template <int NW, int E, int C>
 __device__ __forceinline__ TopkLaneT<typename LaneMask<E>::type> block_select(const uint16_t (&raw)[E], int K,
-                                                                              TopkShared<NW>& sm) {
+                                                                              TopkShared<NW, C>& sm) {
   typedef typename LaneMask<E>::type Mask;
+  constexpr bool kWide = C == kTopkCopiesWide;
+  static_assert(!kWide || (NW % 4 == 0 && 32 % (NW / 4) == 0), "the copies are summed by NW/4 groups of 256 lanes");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- pass 1: top 8 key bits
-  unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (kTopkCopies - 1)) * kTopkCopyStride;
+  unsigned* mine = sm.hist + (static_cast<unsigned>(lane) & (C - 1)) * TopkHist1<C>::stride;
 #pragma unroll
   for (int q = 0; q < E; ++q)
     atomicAdd(&mine[(raw[q] & 0x7FFFu) >> 7], 1u);
   __syncthreads();
+  if constexpr (kWide) {
+    // lane group g = tid / 256 sums its 32 / (NW/4) copies of bin tid % 256 (consecutive lanes, consecutive banks)
+    constexpr int kGroups = NW / 4, kPer = kTopkCopiesWide / kGroups;
+    const int bin = tid & 255, grp = tid >> 8;
+    unsigned sum = 0;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) sum += sm.hist[(grp * kPer + k) * kTopkCopyStrideWide + bin];
+    sm.part[grp * 256 + bin] = sum;
+    __syncthreads();
+  }
   int bin1;
   unsigned above1;
   if (kTopkAllWavesScan1 || wave == 0) {
     // lane covers 4 bins counted from the top: position p = 4*lane + q is bin 255 - p; its four
     // counts of one copy are one aligned 16-byte read
     unsigned c[4] = {0u, 0u, 0u, 0u};
+    if constexpr (kWide) {
 #pragma unroll
-    for (int k = 0; k < kTopkCopies; ++k) {
-      const uint4 v = *reinterpret_cast<const uint4*>(sm.hist + k * kTopkCopyStride + 252 - 4 * lane);
-      c[0] += v.w; c[1] += v.z; c[2] += v.y; c[3] += v.x;
+      for (int k = 0; k < NW / 4; ++k) {
+        const uint4 v = *reinterpret_cast<const uint4*>(sm.part + k * 256 + 252 - 4 * lane);
+        c[0] += v.w; c[1] += v.z; c[2] += v.y; c[3] += v.x;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kTopkCopies; ++k) {
+        const uint4 v = *reinterpret_cast<const uint4*>(sm.hist + k * kTopkCopyStride + 252 - 4 * lane);
+        c[0] += v.w; c[1] += v.z; c[2] += v.y; c[3] += v.x;
+      }
     }
     const unsigned local = (c[0] + c[1]) + (c[2] + c[3]);
     const unsigned need = static_cast<unsigned>(K);
