@@ -48,17 +48,21 @@ def build_library(verbose: bool = False) -> str:
 
 
 def build_diag(verbose: bool = False) -> str:
-    """Compile the diagnostic program csrc/diag_phase_clock.hip (the projection kernels with their phase
-    clocks compiled in, plus a small driver) into _build/diag_phase_clock.  Not needed by the library."""
+    """Compile the diagnostic programs csrc/diag_phase_clock.hip (the batch-1 projection kernels) and
+    csrc/diag_batched_clock.hip (the batched projection and the per-token Top-K kernel), each the library's own
+    kernels with their phase clocks compiled in plus a small driver, into _build/.  Not needed by the library."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    exe = os.path.join(objdir, "diag_phase_clock")
-    cmd = [hipcc()] + [f for f in FLAGS if f not in ("-shared", "-fPIC")] + [os.path.join(CSRC, "diag_phase_clock.hip"),
-                                                                             "-o", exe]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, cwd=CSRC)
-    return exe
+    exes = []
+    for name in ("diag_phase_clock", "diag_batched_clock"):
+        exe = os.path.join(objdir, name)
+        cmd = [hipcc()] + [f for f in FLAGS if f not in ("-shared", "-fPIC")] + [os.path.join(CSRC, name + ".hip"),
+                                                                                 "-o", exe]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True, cwd=CSRC)
+        exes.append(exe)
+    return " ".join(exes)
 
 
 if __name__ == "__main__":
