@@ -76,6 +76,7 @@ int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t s
     side.chunk = ps.chunk;
     side.G = ps.G;
     side.nstrips = ps.nstrips;
+    side.wps = ps.wps;
     side.counters = counters + slots * kCounterStride;
     side.partial = reinterpret_cast<float*>(partial + pbytes);
     slots += groups * ps.nstrips;
@@ -88,6 +89,7 @@ int run_batched(BatchArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t s
   a.chunk = p.chunk;
   a.G = p.G;
   a.nstrips = p.nstrips;
+  a.wps = p.wps;
   a.counters = counters;
   a.partial = reinterpret_cast<float*>(partial);
   pr.main = a;

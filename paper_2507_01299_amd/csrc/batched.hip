@@ -49,8 +49,12 @@ struct Geometry {
   int g_first, g_last;    // workgroups that contribute to the strip
 };
 
-__device__ __forceinline__ Geometry strip_geometry(int s, int t0, int t1, int K, int chunk) {
-  Geometry q{s, t0, t1, (s * K) / chunk, ((s + 1) * K - 1) / chunk};
+// Workgroup g works on strip g / wps only, rows [(g % wps) * chunk, + chunk) of it (plan_batched: every
+// workgroup of a strip has rows, all but the last one `chunk` of them).
+__device__ __forceinline__ Geometry strip_geometry(int g, int wps, int K, int chunk) {
+  const int s = g / wps;
+  const int t0 = (g - s * wps) * chunk;
+  Geometry q{s, t0, min(K, t0 + chunk), s * wps, s * wps + wps - 1};
   return q;
 }
 
@@ -120,15 +124,10 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
   const int K = a.d_in;
   const int chunk = a.chunk;
 
-  int f0 = g * chunk;
-  const int f1 = min(f0 + chunk, a.nstrips * K);
-  int s = f0 / K;
-  int t0 = f0 - s * K;
-  int seg_no = 0;
-  while (f0 < f1) {
-    const int t1 = min(K, t0 + (f1 - f0));
+  {
+    const Geometry ge = strip_geometry(g, a.wps, K, chunk);
+    const int s = ge.s, t0 = ge.t0, t1 = ge.t1;
     const int n = t1 - t0;
-    const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
     const int col = s * kFStrip + m * 8;
     const bool colv = col < a.d_out;
 
@@ -207,7 +206,7 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
       // slot: [NB][4][16] float pairs; lane m of the first wave holds columns 8m..8m+7
       const size_t slot_floats = static_cast<size_t>(NB) * kFStrip;
       unsigned long long* slot = reinterpret_cast<unsigned long long*>(
-          a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
+          a.partial + (static_cast<size_t>(grp) * a.G + g) * slot_floats);
       unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
       if (rw == 0 && kgrp == 0) {
 #pragma unroll
@@ -235,9 +234,8 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) acc[bb][k] = 0.f;
         for (int gg = ge.g_first + 4 * rw + kgrp; gg <= ge.g_last; gg += 4 * kBRW) {
-          const int sgn = ((gg * chunk) / K != s) ? 1 : 0;
           const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
-              a.partial + ((static_cast<size_t>(grp) * a.G + gg) * 2 + sgn) * slot_floats);
+              a.partial + (static_cast<size_t>(grp) * a.G + gg) * slot_floats);
           unsigned long long v[NB][4];
 #pragma unroll
           for (int bb = 0; bb < NB; ++bb)
@@ -285,11 +283,6 @@ __global__ __launch_bounds__(kBThreads) void skinny_fma_kernel(BatchArgs a) {
           if (b0 + bb < a.B) store_out8<T>(a, b0 + bb, col, acc[bb], scale_s[bb]);
       }
     }
-    __syncthreads();
-    f0 += t1 - t0;
-    s += 1;
-    t0 = 0;
-    seg_no += 1;
   }
 }
 
@@ -336,15 +329,10 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
   const int chunk = a.chunk;
 
   LAROSA_STAMP(0);
-  int f0 = g * chunk;
-  const int f1 = min(f0 + chunk, a.nstrips * K);
-  int s = f0 / K;
-  int t0 = f0 - s * K;
-  int seg_no = 0;
-  while (f0 < f1) {
-    const int t1 = min(K, t0 + (f1 - f0));
+  {
+    const Geometry ge = strip_geometry(g, a.wps, K, chunk);
+    const int s = ge.s, t0 = ge.t0, t1 = ge.t1;
     const int n = t1 - t0;
-    const Geometry ge = strip_geometry(s, t0, t1, K, chunk);
     const int colbase = s * kMStrip + 8 * m;   // this lane's 8 columns (A operand)
     const bool colv = colbase < a.d_out;
 
@@ -412,9 +400,14 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
     LAROSA_STAMP(1);
     const int n_s = ge.g_last - ge.g_first + 1;
     const size_t slot_floats = static_cast<size_t>(NTB) * 16 * kMStrip;
-    unsigned long long* slot = reinterpret_cast<unsigned long long*>(
-        a.partial + ((static_cast<size_t>(grp) * a.G + g) * 2 + seg_no) * slot_floats);
     unsigned* ctr = a.counters + (static_cast<size_t>(grp) * a.nstrips + s) * kCounterStride;
+    // every partial of this token group as one buffer (slot of workgroup w at byte w * slot bytes; a thread's 16 bytes of token block tb at tb * 8 KiB + tid * 16 within it);
+    // 16-byte accesses with the sc1 cache policy are coherent across the chip, see gemv_core.hpp
+    const int slot_bytes = NTB * 8192;
+    const __amdgpu_buffer_rsrc_t slots = __builtin_amdgcn_make_buffer_rsrc(
+        a.partial + static_cast<size_t>(grp) * a.G * slot_floats, 0, a.G * slot_bytes, 0x00027000);
+    constexpr int kCoherent = 16;
+    const int my_slot = g * slot_bytes;
 
     // Sum the 8 row-waves of token block tb: waves 0-3 write their tiles, waves 4-7 add theirs on
     // top, then every thread adds the four tiles for its two float pairs (pair q: token q / 64,
@@ -484,13 +477,9 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
       for (int tb = 0; tb < NTB; ++tb) {
         float2 sm[2];
         reduce_tb(tb, sm);
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          const unsigned long long v = static_cast<unsigned long long>(__float_as_uint(sm[k].x)) |
-                                       (static_cast<unsigned long long>(__float_as_uint(sm[k].y)) << 32);
-          __hip_atomic_store(slot + static_cast<size_t>(tb) * 1024 + tid + k * kBThreads, v, __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-        }
+        // the thread's two float pairs of the block as one 16-byte chip-coherent store
+        const u32x4 v = {__float_as_uint(sm[0].x), __float_as_uint(sm[0].y), __float_as_uint(sm[1].x), __float_as_uint(sm[1].y)};
+        __builtin_amdgcn_raw_buffer_store_b128(v, slots, my_slot + tb * 8192 + tid * 16, 0, kCoherent);
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
@@ -509,26 +498,20 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
           float2 sum[2];
           sum[0] = sum[1] = make_float2(0.f, 0.f);
           for (int gg = ge.g_first; gg <= ge.g_last; gg += 8) {
-            unsigned long long v[8][2];
+            u32x4 v[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-              const int g2 = min(gg + q, ge.g_last);
-              const int sgn = ((g2 * chunk) / K != s) ? 1 : 0;
-              const unsigned long long* p = reinterpret_cast<const unsigned long long*>(
-                  a.partial + ((static_cast<size_t>(grp) * a.G + g2) * 2 + sgn) * slot_floats);
-#pragma unroll
-              for (int k = 0; k < 2; ++k)
-                v[q][k] = __hip_atomic_load(p + static_cast<size_t>(tb) * 1024 + tid + k * kBThreads, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);
+              if (gg + q <= ge.g_last) {          // uniform over the workgroup: no partial is read twice
+                v[q] = __builtin_amdgcn_raw_buffer_load_b128(slots, (gg + q) * slot_bytes + tb * 8192 + tid * 16, 0, kCoherent);
+              }
             }
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
               if (gg + q <= ge.g_last) {
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                  sum[k].x += __uint_as_float(static_cast<unsigned>(v[q][k] & 0xFFFFFFFFull));
-                  sum[k].y += __uint_as_float(static_cast<unsigned>(v[q][k] >> 32));
-                }
+                sum[0].x += __uint_as_float(v[q].x);
+                sum[0].y += __uint_as_float(v[q].y);
+                sum[1].x += __uint_as_float(v[q].z);
+                sum[1].y += __uint_as_float(v[q].w);
               }
             }
           }
@@ -536,11 +519,6 @@ __device__ __forceinline__ void skinny_mfma_body(const BatchArgs& a, int g, int 
         }
       }
     }
-    __syncthreads();
-    f0 += t1 - t0;
-    s += 1;
-    t0 = 0;
-    seg_no += 1;
   }
   LAROSA_STAMP(5);
 }
@@ -573,7 +551,14 @@ hipError_t launch_batched_t(const BatchPair& p, hipStream_t st) {
       hipLaunchKernelGGL((skinny_fma_kernel<T, 4>), dim3(a.G, (a.B + 3) / 4), block, 0, st, a);
     }
   } else if (a.B <= 16) {
-    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G + p.side_G, 1), block, 0, st, p);
+    size_t pad = 0;
+    if (tuning().lds_pad > 0 && a.G + p.side_G <= 256) {
+      pad = static_cast<size_t>(tuning().lds_pad);
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<T, 1>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pad)) != hipSuccess)
+        return hipErrorInvalidValue;
+    }
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G + p.side_G, 1), block, pad, st, p);
   } else {
     hipLaunchKernelGGL((skinny_mfma_kernel<T, 2>), dim3(a.G + p.side_G, (a.B + 31) / 32), block, 0, st, p);
   }
@@ -595,16 +580,19 @@ GemvPlan plan_batched(int d_in, int d_out, bool mfma, int g_hint) {
   GemvPlan p;
   p.strip_cols = 128;   // both batched kernels work on 128-column strips
   p.nstrips = (d_out + p.strip_cols - 1) / p.strip_cols;
-  const long T = static_cast<long>(p.nstrips) * d_in;
-  long G = g_hint > 0 ? g_hint : batched_g_total();             // one workgroup per compute unit
-  if (G < p.nstrips) G = p.nstrips;
-  long chunk = (T + G - 1) / G;
-  chunk = (chunk + 15) / 16 * 16;                                // whole 16-row tiles; keeps row starts 8-aligned
+  // one workgroup per compute unit: each strip gets the same number of workgroups, each of those an equal run
+  // of whole 16-row tiles (keeps row starts 8-aligned), so a workgroup never works on two strips
+  long G = g_hint > 0 ? g_hint : batched_g_total();
+  long wps = G / p.nstrips;
+  if (wps < 1) wps = 1;
+  long chunk = (d_in + wps - 1) / wps;
+  chunk = (chunk + 15) / 16 * 16;
   if (!mfma && chunk > kBatchChunkMax) chunk = kBatchChunkMax;   // LDS staging of the coefficients
-  if (chunk > d_in) chunk = d_in;                                // a workgroup touches at most two strips
+  wps = (d_in + chunk - 1) / chunk;
   p.chunk = static_cast<int>(chunk);
-  p.G = static_cast<int>((T + chunk - 1) / chunk);
-  p.partial_floats = static_cast<size_t>(p.G) * 2 * p.strip_cols;  // per token
+  p.wps = static_cast<int>(wps);
+  p.G = static_cast<int>(p.nstrips * wps);
+  p.partial_floats = static_cast<size_t>(p.G) * p.strip_cols;  // per token
   return p;
 }
 

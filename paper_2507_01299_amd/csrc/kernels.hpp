@@ -46,6 +46,7 @@ struct Tuning {
   int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
   int side_g = 0;             // workgroups of that adapter; 0 = by size (both jobs resident at once: at most 512 slots)
   int hinted = 1;             // decoder layer: 1 = the down projection takes its threshold from histograms that the gate|up launch builds
+  int lds_pad = 0;            // experiment: bytes of unused dynamic LDS per workgroup of a launch of at most 256 workgroups
 };
 Tuning& tuning();
 
@@ -118,8 +119,8 @@ struct BatchArgs {
   const uint16_t* C;          // [B, d_in] coefficients
   uint16_t* y;                // [B, d_out]
   int d_in, d_out, B;
-  int chunk, G, nstrips;      // work split over (strip, row) pairs, rows = all d_in
-  float* partial;             // [groups][G][2][tokens per group][512] fp32
+  int chunk, G, nstrips, wps; // strip g / wps, rows [(g % wps) * chunk, + chunk) of all d_in
+  float* partial;             // [groups][G][tokens per group][128] fp32
   unsigned* counters;         // [groups][nstrips] arrival counters
   const uint16_t* coef_scale; // as in GemvArgs
   const uint16_t* rms_src;
