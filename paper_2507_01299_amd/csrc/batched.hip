@@ -551,14 +551,7 @@ hipError_t launch_batched_t(const BatchPair& p, hipStream_t st) {
       hipLaunchKernelGGL((skinny_fma_kernel<T, 4>), dim3(a.G, (a.B + 3) / 4), block, 0, st, a);
     }
   } else if (a.B <= 16) {
-    size_t pad = 0;
-    if (tuning().lds_pad > 0 && a.G + p.side_G <= 256) {
-      pad = static_cast<size_t>(tuning().lds_pad);
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<T, 1>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pad)) != hipSuccess)
-        return hipErrorInvalidValue;
-    }
-    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G + p.side_G, 1), block, pad, st, p);
+    hipLaunchKernelGGL((skinny_mfma_kernel<T, 1>), dim3(a.G + p.side_G, 1), block, 0, st, p);
   } else {
     hipLaunchKernelGGL((skinny_mfma_kernel<T, 2>), dim3(a.G + p.side_G, (a.B + 31) / 32), block, 0, st, p);
   }

@@ -39,7 +39,6 @@ int main(int argc, char** argv) {
     else if (!strcmp(argv[i], "--reps") && i + 1 < argc) reps = atoi(argv[++i]);
     else if (!strcmp(argv[i], "--only") && i + 1 < argc) only = argv[++i];
     else if (!strcmp(argv[i], "--batch") && i + 1 < argc) B = atoi(argv[++i]);
-    else if (!strcmp(argv[i], "--lds-pad") && i + 1 < argc) tuning().lds_pad = atoi(argv[++i]);
   }
   if (B < 2 || B > 32 || reps < 1 || reps > 1000 || G < 0 || G > 2048) { printf("--batch 2..32, --reps 1..1000, --g 0..2048\n"); return 1; }
   const int maxwg = 4096;
@@ -48,8 +47,7 @@ int main(int argc, char** argv) {
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
 
   // ---- batched projections ------------------------------------------------------------------------------------
-  struct Shape { const char* n; int d_in, d_out; } shapes[] = {{"o", 4096, 4096}, {"qkv", 4096, 6144}, {"down", 14336, 4096}, {"gu", 4096, 28672},
-                                                                  {"o+", 4096, 4224}, {"down+", 14336, 4224}, {"gu+", 4096, 28800}};
+  struct Shape { const char* n; int d_in, d_out; } shapes[] = {{"o", 4096, 4096}, {"qkv", 4096, 6144}, {"down", 14336, 4096}, {"gu", 4096, 28672}};
   unsigned* ctr; CK(hipMalloc(&ctr, 1 << 20)); CK(hipMemset(ctr, 0, 1 << 20));
   float* partial; CK(hipMalloc(&partial, 256u << 20));
   for (auto& sh : shapes) {

@@ -46,7 +46,6 @@ struct Tuning {
   int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
   int side_g = 0;             // workgroups of that adapter; 0 = by size (both jobs resident at once: at most 512 slots)
   int hinted = 1;             // decoder layer: 1 = the down projection takes its threshold from histograms that the gate|up launch builds
-  int lds_pad = 0;            // experiment: bytes of unused dynamic LDS per workgroup of a launch of at most 256 workgroups
 };
 Tuning& tuning();
 

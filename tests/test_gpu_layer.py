@@ -286,6 +286,27 @@ def test_layer_in_a_hip_graph_replays_to_the_eager_bits(api, B, form):
         assert torch.equal(other.view(torch.int16), eager.view(torch.int16))
 
 
+@pytest.mark.parametrize("B", [1, 3, 17])
+@pytest.mark.parametrize("form", ["shortcut", "explicit"])
+def test_untraced_run_gives_the_traced_output(api, B, form):
+    """A run without trace buffers (what the bench times) skips the stores of the intermediate tensors and, in the
+    batched path, of the index lists; the layer output must keep its bits, and the traced run is the one the
+    oracle checks stage by stage."""
+    shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "bf16")
+    if form == "shortcut":
+        layers, bits, Qa, _, src = cases.build_shortcut_stack(shape, 1, 0.4, seed=91, n_cal=1024)
+        case = cases.LayerCase(shape, bits[0], layers[0], {}, src)
+    else:
+        case = cases.build_block_layer(shape, 0.4, seed=91, n_cal=1024, with_adapter=True)
+    print(f"untraced vs traced B={B} form={form}", flush=True)
+    xb, traced, tr, dl, ws = _run_layer(api, case, B, seed=6)
+    check_layer_trace(case.layer, xb, tr, traced)
+    plain = torch.zeros_like(traced)
+    api.layer_forward(dl, to_dev(xb, "bf16"), plain, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(plain.view(torch.int16), traced.view(torch.int16))
+
+
 def test_config1_llama2_7b_shortcut_form_full_size(api):
     """The benchmark layer in the deployed block-level form: rotations absorbed, two 4096 x 4096
     residual adapters on the shortcuts, 40 % sparsity, batch 1."""
