@@ -191,6 +191,7 @@ struct ContractionArgs {
   int accumulate;           // C32 only: add to what is there
   int symmetric;            // A == B, M == N: compute tiles on or above the diagonal, store both halves
   int tiles_m, tiles_n, patches_m, patches_n;   // filled in by launch_contraction
+  long a_elements, b_elements;                  // extent of each operand over all its terms (filled in as well)
 };
 hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s);
 // number of 16-bit terms an fp32 operand is split into (2 for f16, 3 for bf16)

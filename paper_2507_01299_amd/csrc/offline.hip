@@ -52,17 +52,19 @@ template <> struct Mfma<BF16> {
   }
 };
 
-// k-major source P[k][ld]: rows k0 + 2 kp, k0 + 2 kp + 1, columns c0 + 8 g .. + 7 -> r0, r1.
-__device__ __forceinline__ void load_kmajor(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int c0, int cols,
-                                            int g, int kp, uint4& r0, uint4& r1) {
-  r0 = make_uint4(0, 0, 0, 0);
-  r1 = r0;
-  const int c = c0 + 8 * g;
-  const int k = k0 + 2 * kp;
-  if (c < cols) {
-    if (k < Kd) r0 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k) * ld + c);
-    if (k + 1 < Kd) r1 = *reinterpret_cast<const uint4*>(P + static_cast<long>(k + 1) * ld + c);
-  }
+// Operand loads go through buffer resources that span the whole (multi-term) operand: a 16-byte load whose
+// offset lies at or beyond the operand's size returns zeros, so rows past Kd need no test, and a lane whose
+// columns lie outside the matrix carries the offset kOutside for good.  Per k-tile a load then costs one
+// add (lane offset + the tile's scalar offset) and no branch.
+constexpr uint32_t kOutside = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_buffer(const uint16_t* p, long elements) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p), 0, static_cast<int>(elements * 2), 0x00027000);
+}
+
+__device__ __forceinline__ uint4 load16(__amdgpu_buffer_rsrc_t buf, uint32_t lane_off, uint32_t tile_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(buf, static_cast<int>(lane_off + tile_off), 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 __device__ __forceinline__ void store_kmajor(uint32_t* tile, const uint4& r0, const uint4& r1, int g, int kp) {
@@ -70,18 +72,9 @@ __device__ __forceinline__ void store_kmajor(uint32_t* tile, const uint4& r0, co
   const uint32_t b[4] = {r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    tile[(8 * g + 2 * q) * kRowDwords + kp] = (a[q] & 0xFFFFu) | (b[q] << 16);
-    tile[(8 * g + 2 * q + 1) * kRowDwords + kp] = (a[q] >> 16) | (b[q] & 0xFFFF0000u);
+    tile[(8 * g + 2 * q) * kRowDwords + kp] = __builtin_amdgcn_perm(b[q], a[q], 0x05040100u);       // a.lo | b.lo << 16
+    tile[(8 * g + 2 * q + 1) * kRowDwords + kp] = __builtin_amdgcn_perm(b[q], a[q], 0x07060302u);   // a.hi | b.hi << 16
   }
-}
-
-// k-contiguous source P[m][ld]: 16 bytes (8 k) of row m0 + row at k0 + 8 kq.
-__device__ __forceinline__ uint4 load_kcontig(const uint16_t* __restrict__ P, long ld, int k0, int Kd, int m0, int rows,
-                                              int row, int kq) {
-  const int k = k0 + 8 * kq;
-  const int m = m0 + row;
-  if (k < Kd && m < rows) return *reinterpret_cast<const uint4*>(P + static_cast<long>(m) * ld + k);
-  return make_uint4(0, 0, 0, 0);
 }
 
 __device__ __forceinline__ void store_kcontig(uint32_t* tile, const uint4& r, int row, int kq) {
@@ -155,20 +148,52 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
   const int ktiles = (a.Kd + kKTile - 1) / kKTile;
   const int iters = ktiles * a.npairs;
 
-  auto fetch = [&](int it, Staged<TN>& st) {
-    const int p = it / ktiles;
-    const int k0 = (it - p * ktiles) * kKTile;
-    const uint16_t* Ap = a.A + a.pa[p] * a.a_term_stride;
-    const uint16_t* Bp = a.B + a.pb[p] * a.b_term_stride;
-    if (A_KMAJOR) {
-      load_kmajor(Ap, a.M, k0, a.Kd, m0, a.M, g, kp, st.a[0], st.a[1]);
-      load_kmajor(Ap, a.M, k0, a.Kd, m0, a.M, g + 16, kp, st.a[2], st.a[3]);
-    } else {
+  // lane offsets (bytes) into the operands, fixed for the whole kernel
+  const __amdgpu_buffer_rsrc_t bufA = operand_buffer(a.A, a.a_elements);
+  const __amdgpu_buffer_rsrc_t bufB = operand_buffer(a.B, a.b_elements);
+  uint32_t offA[4], offB[TN / 64];
+  if (A_KMAJOR) {   // rows 2 kp, 2 kp + 1 of the k-tile, columns m0 + 8 g .. and m0 + 8 (g + 16) ..
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st.a[r] = load_kcontig(Ap, a.Kd, k0, a.Kd, m0, a.M, (t >> 2) + 64 * r, t & 3);
+    for (int h = 0; h < 2; ++h) {
+      const int c = m0 + 8 * (g + 16 * h);
+      offA[2 * h] = c < a.M ? static_cast<uint32_t>((2 * kp * a.M + c) * 2) : kOutside;
+      offA[2 * h + 1] = c < a.M ? offA[2 * h] + static_cast<uint32_t>(a.M * 2) : kOutside;
     }
-    load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g, kp, st.b[0], st.b[1]);
-    if (TN == 256) load_kmajor(Bp, a.N, k0, a.Kd, n0, a.N, g + 16, kp, st.b[NJ - 2], st.b[NJ - 1]);
+  } else {          // row m0 + t / 4 + 64 r, k values 8 (t % 4) .. + 7 of the k-tile
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = m0 + (t >> 2) + 64 * r;
+      offA[r] = m < a.M ? static_cast<uint32_t>((m * a.Kd + 8 * (t & 3)) * 2) : kOutside;
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < TN / 128; ++h) {
+    const int c = n0 + 8 * (g + 16 * h);
+    offB[2 * h] = c < a.N ? static_cast<uint32_t>((2 * kp * a.N + c) * 2) : kOutside;
+    offB[2 * h + 1] = c < a.N ? offB[2 * h] + static_cast<uint32_t>(a.N * 2) : kOutside;
+  }
+
+  // iteration it = (term pair p, k-tile kt), kt fastest; the scalar offsets of its tile
+  int f_p = 0, f_kt = 0;
+  auto fetch = [&](Staged<TN>& st) {
+    const int k0 = f_kt * kKTile;
+    const uint32_t ta = static_cast<uint32_t>((a.pa[f_p] * a.a_term_stride + (A_KMAJOR ? static_cast<long>(k0) * a.M : k0)) * 2);
+    const uint32_t tb = static_cast<uint32_t>((a.pb[f_p] * a.b_term_stride + static_cast<long>(k0) * a.N) * 2);
+    // rows of this k-tile at or past Kd are zero (with several terms the bytes behind a term are the next term's)
+    const int kr = a.Kd - k0;
+    const bool row0 = 2 * kp < kr, row1 = 2 * kp + 1 < kr;
+    if (A_KMAJOR) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st.a[r] = load16(bufA, ((r & 1) ? row1 : row0) ? offA[r] : kOutside, ta);
+    } else {
+      // a row's k values past Kd belong to the next row: those lanes read outside instead
+      const bool in = k0 + 8 * (t & 3) < a.Kd;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) st.a[r] = load16(bufA, in ? offA[r] : kOutside, ta);
+    }
+#pragma unroll
+    for (int r = 0; r < TN / 64; ++r) st.b[r] = load16(bufB, ((r & 1) ? row1 : row0) ? offB[r] : kOutside, tb);
+    if (++f_kt == ktiles) { f_kt = 0; ++f_p; }
   };
   auto stash = [&](int buf, const Staged<TN>& st) {
     if (A_KMAJOR) {
@@ -181,39 +206,41 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
     store_kmajor(lds_b[buf], st.b[0], st.b[1], g, kp);
     if (TN == 256) store_kmajor(lds_b[buf], st.b[NJ - 2], st.b[NJ - 1], g + 16, kp);
   };
-  auto compute = [&](int buf) {
+  // one 16-deep half (s = 0, 1) of the k-tile in LDS buffer buf
+  auto compute_half = [&](int buf, int s) {
     const uint32_t* At = lds_a[buf];
     const uint32_t* Bt = lds_b[buf];
+    const int dw = s * 8 + (lane >> 5) * 4;
+    u32x4 av[4], bv[NJ];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int dw = s * 8 + (lane >> 5) * 4;
-      u32x4 av[4], bv[NJ];
+    for (int i = 0; i < 4; ++i) av[i] = read_operand(At, wm * 128 + i * 32 + (lane & 31), dw);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) av[i] = read_operand(At, wm * 128 + i * 32 + (lane & 31), dw);
+    for (int j = 0; j < NJ; ++j) bv[j] = read_operand(Bt, wn * (TN / 2) + j * 32 + (lane & 31), dw);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) bv[j] = read_operand(Bt, wn * (TN / 2) + j * 32 + (lane & 31), dw);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i][j] = Mfma<T>::run(av[i], bv[j], acc[i][j]);
-    }
+      for (int j = 0; j < NJ; ++j) acc[i][j] = Mfma<T>::run(av[i], bv[j], acc[i][j]);
   };
 
   // Tile it is computed from LDS buffer it & 1 while the loads of tile it + 2 are in flight and tile
   // it + 1 (loaded one step earlier) moves from registers to the other buffer: one barrier per tile.
   Staged<TN> s0, s1;
-  fetch(0, s0);
+  fetch(s0);
   stash(0, s0);
-  if (iters > 1) fetch(1, s1);
+  if (iters > 1) fetch(s1);
   __syncthreads();
   for (int it = 0; it < iters; it += 2) {
-    if (it + 2 < iters) fetch(it + 2, s0);
-    compute(0);
+    // (moving the stash between the two halves of the products, so that its writes complete behind matrix
+    // instructions, measured no faster)
+    if (it + 2 < iters) fetch(s0);
+    compute_half(0, 0);
+    compute_half(0, 1);
     if (it + 1 < iters) stash(1, s1);
     __syncthreads();
     if (it + 1 < iters) {
-      if (it + 3 < iters) fetch(it + 3, s1);
-      compute(1);
+      if (it + 3 < iters) fetch(s1);
+      compute_half(1, 0);
+      compute_half(1, 1);
       if (it + 2 < iters) stash(0, s0);
       __syncthreads();
     }
@@ -293,6 +320,15 @@ hipError_t launch_tiles(ContractionArgs a, hipStream_t s) {
   a.tiles_n = (a.N + TN - 1) / TN;
   a.patches_m = (a.tiles_m + kPatchM - 1) / kPatchM;
   a.patches_n = (a.tiles_n + kPatchN - 1) / kPatchN;
+  // the operands are addressed with 32-bit byte offsets from their first term
+  int ta = 0, tb = 0;
+  for (int i = 0; i < a.npairs; ++i) {
+    ta = a.pa[i] > ta ? a.pa[i] : ta;
+    tb = a.pb[i] > tb ? a.pb[i] : tb;
+  }
+  a.a_elements = ta * a.a_term_stride + static_cast<long>(a.Kd) * a.M;
+  a.b_elements = tb * a.b_term_stride + static_cast<long>(a.Kd) * a.N;
+  if (a.a_elements * 2 >= 0x7FFFFFF0L || a.b_elements * 2 >= 0x7FFFFFF0L) return hipErrorInvalidValue;
   const long patches = static_cast<long>(a.patches_m) * a.patches_n;
   const long grid = (patches + 7) / 8 * 8 * 32;
   if (grid > 0x7FFFFFFFL) return hipErrorInvalidValue;
