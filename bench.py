@@ -80,8 +80,11 @@ def offline_report(args, api, torch, shape, cfg, dev):
         return (torch.randn(r, c, generator=gen, device=dev, dtype=torch.float32) * s).to(td)
 
     X = gauss(n, d, 1.0)
-    Q = torch.linalg.qr(torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32))[0].contiguous()
-    Q2 = torch.linalg.qr(torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32))[0].contiguous()
+    def orthogonal():   # (--host-solver: the vendor's device QR does not survive hardware-counter collection)
+        g = torch.randn(d, d, generator=gen, device=dev, dtype=torch.float32)
+        return (torch.linalg.qr(g.cpu())[0].to(dev) if args.host_solver else torch.linalg.qr(g)[0]).contiguous()
+
+    Q, Q2 = orthogonal(), orthogonal()
     sc = api.OfflineScratch(d, shape.dtype)
     C = torch.empty(d, d, dtype=torch.float32, device=dev)
     Wqkv, Wgu, Wo, Wdown = gauss(d, d_q + 2 * d_kv), gauss(d, 2 * d_ff), gauss(d_q, d), gauss(d_ff, d)

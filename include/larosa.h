@@ -270,7 +270,8 @@ int larosa_threshold_select(const void* h, int B, int d, float eps, larosa_dtype
  * key 8 = with key 9 = 0: widest MLP intermediate vector whose Top-K runs inside the down projection's
  * workgroups (wider ones are selected once by the Top-K kernel),
  * key 9 = batch-1 decoder layer: the down projection takes its Top-K threshold from key histograms
- * that the gate|up launch builds (1, default) or selects for itself (0).
+ * that the gate|up launch builds (1, default) or selects for itself (0),
+ * key 10 = workgroup tile of the offline contractions: 0 = chosen by size (default), 1 = 256 x 128, 2 = 256 x 256.
  * Returns LAROSA_EINVAL for an unknown key or a value out of range. */
 int larosa_set_tuning(int key, int value);
 

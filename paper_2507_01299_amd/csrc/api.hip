@@ -951,6 +951,10 @@ int larosa_set_tuning(int key, int value) {
       if (value < 0 || value > 1) return LAROSA_EINVAL;
       tuning().hinted = value;
       return LAROSA_OK;
+    case 10:
+      if (value < 0 || value > 2) return LAROSA_EINVAL;
+      tuning().contraction_tiles = value;
+      return LAROSA_OK;
     default:
       return LAROSA_EINVAL;
   }

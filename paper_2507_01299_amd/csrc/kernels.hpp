@@ -46,6 +46,7 @@ struct Tuning {
   int fused_max_width = 16384;    // decoder layer: widest block input selected inside every projection workgroup
   int side_g = 0;             // workgroups of that adapter; 0 = by size (both jobs resident at once: at most 512 slots)
   int hinted = 1;             // decoder layer: 1 = the down projection takes its threshold from histograms that the gate|up launch builds
+  int contraction_tiles = 0;  // offline contractions: 0 = workgroup tile by size, 1 = 256 x 128, 2 = 256 x 256
 };
 Tuning& tuning();
 

@@ -98,11 +98,11 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// One k-tile of both operands in a thread's registers.
-template <int TN>
+// One k-tile of both operands in a thread's registers: NA / NB 16-byte pieces of A / B.
+template <int NA, int NB>
 struct Staged {
-  uint4 a[4];
-  uint4 b[TN / 64];
+  uint4 a[NA];
+  uint4 b[NB];
 };
 
 // Is the 256 x TN tile that holds element (row, col) left out of a symmetric product?
@@ -111,10 +111,18 @@ __device__ __forceinline__ bool tile_skipped(int row, int col) {
   return TN * (col / TN + 1) <= kTileM * (row / kTileM);
 }
 
-// TN = 128 is the instantiated shape: 4 x 2 instruction tiles per wave, two workgroups per CU.
-template <typename T, bool A_KMAJOR, int TN>
-__global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(ContractionArgs a) {
-  constexpr int NJ = TN / 64;                    // instruction tiles of a wave along n
+// A workgroup of NW waves owns a 256 x TN tile of C; every wave a 128 x 64 part (4 x 2 instruction tiles):
+// NW = 4, TN = 128 (two workgroups per compute unit) or NW = 8, TN = 256 (one).  The larger tile moves a third
+// fewer operand bytes from the L2 per flop, which is what bounds the product.
+template <typename T, bool A_KMAJOR, int TN, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void contraction_kernel(ContractionArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int WN = NW / 2;                     // waves along n (two along m)
+  constexpr int NJ = TN / (32 * WN);             // 32-column instruction tiles of a wave along n
+  static_assert(NJ == 2, "a wave owns 128 x 64");
+  constexpr int GA = 32 * 16 / NT;               // 8-column groups of A per thread (k-major: two rows each)
+  constexpr int GB = (TN / 8) * 16 / NT;         // the same for B
+  constexpr int NA = 2 * GA, NB = 2 * GB;
   constexpr int kTileN = TN;
   constexpr int kTileDwordsB = TN * kRowDwords;
   __shared__ uint32_t lds_a[2][kTileDwordsA];
@@ -133,9 +141,10 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
   if (a.symmetric && tile_skipped<TN>(m0, n0)) return;
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  const int g = (lane & 7) + 8 * (w & 1);
-  const int kp = (lane >> 3) + 8 * (w >> 1);
-  const int wm = w >> 1, wn = w & 1;    // wave tile: rows wm * 128 .. + 127, columns wn * TN/2 .. + TN/2 - 1
+  constexpr int kGroupsPerPass = NT / 16;        // 8-column groups that the workgroup's threads cover at once
+  const int g = (lane & 7) + 8 * (w % (NW / 2));
+  const int kp = (lane >> 3) + 8 * (w / (NW / 2));
+  const int wm = w / WN, wn = w % WN;   // wave tile: rows wm * 128 .. + 127, columns wn * 64 .. + 63
 
   float16v acc[4][NJ];
 #pragma unroll
@@ -151,31 +160,31 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
   // lane offsets (bytes) into the operands, fixed for the whole kernel
   const __amdgpu_buffer_rsrc_t bufA = operand_buffer(a.A, a.a_elements);
   const __amdgpu_buffer_rsrc_t bufB = operand_buffer(a.B, a.b_elements);
-  uint32_t offA[4], offB[TN / 64];
-  if (A_KMAJOR) {   // rows 2 kp, 2 kp + 1 of the k-tile, columns m0 + 8 g .. and m0 + 8 (g + 16) ..
+  uint32_t offA[NA], offB[NB];
+  if (A_KMAJOR) {   // rows 2 kp, 2 kp + 1 of the k-tile, columns m0 + 8 (g + h * groups per pass) ..
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int c = m0 + 8 * (g + 16 * h);
+    for (int h = 0; h < GA; ++h) {
+      const int c = m0 + 8 * (g + kGroupsPerPass * h);
       offA[2 * h] = c < a.M ? static_cast<uint32_t>((2 * kp * a.M + c) * 2) : kOutside;
       offA[2 * h + 1] = c < a.M ? offA[2 * h] + static_cast<uint32_t>(a.M * 2) : kOutside;
     }
-  } else {          // row m0 + t / 4 + 64 r, k values 8 (t % 4) .. + 7 of the k-tile
+  } else {          // row m0 + t / 4 + (NT / 4) r, k values 8 (t % 4) .. + 7 of the k-tile
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = m0 + (t >> 2) + 64 * r;
+    for (int r = 0; r < NA; ++r) {
+      const int m = m0 + (t >> 2) + (NT / 4) * r;
       offA[r] = m < a.M ? static_cast<uint32_t>((m * a.Kd + 8 * (t & 3)) * 2) : kOutside;
     }
   }
 #pragma unroll
-  for (int h = 0; h < TN / 128; ++h) {
-    const int c = n0 + 8 * (g + 16 * h);
+  for (int h = 0; h < GB; ++h) {
+    const int c = n0 + 8 * (g + kGroupsPerPass * h);
     offB[2 * h] = c < a.N ? static_cast<uint32_t>((2 * kp * a.N + c) * 2) : kOutside;
     offB[2 * h + 1] = c < a.N ? offB[2 * h] + static_cast<uint32_t>(a.N * 2) : kOutside;
   }
 
   // iteration it = (term pair p, k-tile kt), kt fastest; the scalar offsets of its tile
   int f_p = 0, f_kt = 0;
-  auto fetch = [&](Staged<TN>& st) {
+  auto fetch = [&](Staged<NA, NB>& st) {
     const int k0 = f_kt * kKTile;
     const uint32_t ta = static_cast<uint32_t>((a.pa[f_p] * a.a_term_stride + (A_KMAJOR ? static_cast<long>(k0) * a.M : k0)) * 2);
     const uint32_t tb = static_cast<uint32_t>((a.pb[f_p] * a.b_term_stride + static_cast<long>(k0) * a.N) * 2);
@@ -184,27 +193,27 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
     const bool row0 = 2 * kp < kr, row1 = 2 * kp + 1 < kr;
     if (A_KMAJOR) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st.a[r] = load16(bufA, ((r & 1) ? row1 : row0) ? offA[r] : kOutside, ta);
+      for (int r = 0; r < NA; ++r) st.a[r] = load16(bufA, ((r & 1) ? row1 : row0) ? offA[r] : kOutside, ta);
     } else {
       // a row's k values past Kd belong to the next row: those lanes read outside instead
       const bool in = k0 + 8 * (t & 3) < a.Kd;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) st.a[r] = load16(bufA, in ? offA[r] : kOutside, ta);
+      for (int r = 0; r < NA; ++r) st.a[r] = load16(bufA, in ? offA[r] : kOutside, ta);
     }
 #pragma unroll
-    for (int r = 0; r < TN / 64; ++r) st.b[r] = load16(bufB, ((r & 1) ? row1 : row0) ? offB[r] : kOutside, tb);
+    for (int r = 0; r < NB; ++r) st.b[r] = load16(bufB, ((r & 1) ? row1 : row0) ? offB[r] : kOutside, tb);
     if (++f_kt == ktiles) { f_kt = 0; ++f_p; }
   };
-  auto stash = [&](int buf, const Staged<TN>& st) {
+  auto stash = [&](int buf, const Staged<NA, NB>& st) {
     if (A_KMAJOR) {
-      store_kmajor(lds_a[buf], st.a[0], st.a[1], g, kp);
-      store_kmajor(lds_a[buf], st.a[2], st.a[3], g + 16, kp);
+#pragma unroll
+      for (int h = 0; h < GA; ++h) store_kmajor(lds_a[buf], st.a[2 * h], st.a[2 * h + 1], g + kGroupsPerPass * h, kp);
     } else {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) store_kcontig(lds_a[buf], st.a[r], (t >> 2) + 64 * r, t & 3);
+      for (int r = 0; r < NA; ++r) store_kcontig(lds_a[buf], st.a[r], (t >> 2) + (NT / 4) * r, t & 3);
     }
-    store_kmajor(lds_b[buf], st.b[0], st.b[1], g, kp);
-    if (TN == 256) store_kmajor(lds_b[buf], st.b[NJ - 2], st.b[NJ - 1], g + 16, kp);
+#pragma unroll
+    for (int h = 0; h < GB; ++h) store_kmajor(lds_b[buf], st.b[2 * h], st.b[2 * h + 1], g + kGroupsPerPass * h, kp);
   };
   // one 16-deep half (s = 0, 1) of the k-tile in LDS buffer buf
   auto compute_half = [&](int buf, int s) {
@@ -215,7 +224,7 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
 #pragma unroll
     for (int i = 0; i < 4; ++i) av[i] = read_operand(At, wm * 128 + i * 32 + (lane & 31), dw);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) bv[j] = read_operand(Bt, wn * (TN / 2) + j * 32 + (lane & 31), dw);
+    for (int j = 0; j < NJ; ++j) bv[j] = read_operand(Bt, wn * 64 + j * 32 + (lane & 31), dw);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -224,7 +233,7 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
 
   // Tile it is computed from LDS buffer it & 1 while the loads of tile it + 2 are in flight and tile
   // it + 1 (loaded one step earlier) moves from registers to the other buffer: one barrier per tile.
-  Staged<TN> s0, s1;
+  Staged<NA, NB> s0, s1;
   fetch(s0);
   stash(0, s0);
   if (iters > 1) fetch(s1);
@@ -252,7 +261,7 @@ __global__ __launch_bounds__(256, TN == 128 ? 2 : 1) void contraction_kernel(Con
   static_for<4 * NJ>([&](auto ij) {
     constexpr int i = decltype(ij)::value / NJ;
     constexpr int j = decltype(ij)::value % NJ;
-    const int n = n0 + wn * (TN / 2) + j * 32 + (lane & 31);
+    const int n = n0 + wn * 64 + j * 32 + (lane & 31);
     if (n < a.N) {
       static_for<4>([&](auto r4c) {
         constexpr int r4 = decltype(r4c)::value;
@@ -314,7 +323,7 @@ hipError_t launch_split_terms(const float* src, uint16_t* dst, long n, float pre
 
 namespace {
 
-template <typename T, bool A_KMAJOR, int TN>
+template <typename T, bool A_KMAJOR, int TN, int NW>
 hipError_t launch_tiles(ContractionArgs a, hipStream_t s) {
   a.tiles_m = (a.M + kTileM - 1) / kTileM;
   a.tiles_n = (a.N + TN - 1) / TN;
@@ -332,17 +341,24 @@ hipError_t launch_tiles(ContractionArgs a, hipStream_t s) {
   const long patches = static_cast<long>(a.patches_m) * a.patches_n;
   const long grid = (patches + 7) / 8 * 8 * 32;
   if (grid > 0x7FFFFFFFL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((contraction_kernel<T, A_KMAJOR, TN>), dim3(static_cast<unsigned>(grid)), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((contraction_kernel<T, A_KMAJOR, TN, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64), 0, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_contraction(ContractionArgs a, bool a_kmajor, bool bf16, hipStream_t s) {
-  // (a 256 x 256 tile with 4 x 4 instruction tiles per wave needs more than the 512 registers of a
-  // lane once two k-tiles of loads are in flight: measured 7x slower through scratch memory)
-  if (bf16) return a_kmajor ? launch_tiles<BF16, true, 128>(a, s) : launch_tiles<BF16, false, 128>(a, s);
-  return a_kmajor ? launch_tiles<F16, true, 128>(a, s) : launch_tiles<F16, false, 128>(a, s);
+  // 256 x 256 tiles (8 waves) where the product has enough of them to fill the chip, else 256 x 128 (4 waves)
+  long big_tiles = static_cast<long>((a.M + 255) / 256) * ((a.N + 255) / 256);
+  if (a.symmetric) big_tiles /= 2;               // tiles below the diagonal are not computed
+  const int forced = tuning().contraction_tiles; // 0: by size, 1: 256 x 128, 2: 256 x 256 (tests)
+  const bool big = forced == 2 || (forced == 0 && big_tiles >= 256);
+  if (big) {
+    if (bf16) return a_kmajor ? launch_tiles<BF16, true, 256, 8>(a, s) : launch_tiles<BF16, false, 256, 8>(a, s);
+    return a_kmajor ? launch_tiles<F16, true, 256, 8>(a, s) : launch_tiles<F16, false, 256, 8>(a, s);
+  }
+  if (bf16) return a_kmajor ? launch_tiles<BF16, true, 128, 4>(a, s) : launch_tiles<BF16, false, 128, 4>(a, s);
+  return a_kmajor ? launch_tiles<F16, true, 128, 4>(a, s) : launch_tiles<F16, false, 128, 4>(a, s);
 }
 
 }  // namespace larosa

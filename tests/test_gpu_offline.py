@@ -27,11 +27,15 @@ SM_TOL = 5e-5
 ULP_FRACTION = 0.02
 
 
-@pytest.fixture(scope="module")
-def api(gpu_device):
+@pytest.fixture(scope="module", params=[0, 2], ids=["tiles-by-size", "tiles-256x256"])
+def api(gpu_device, request):
+    """Every test runs with the workgroup tile chosen by size (256 x 128 at these sizes) and with the 256 x 256
+    tile that large products get forced on."""
     from paper_2507_01299_amd import api as A
     A.lib()
-    return A
+    A.set_tuning(10, request.param)
+    yield A
+    A.set_tuning(10, 0)
 
 
 def _ordered(bits: np.ndarray) -> np.ndarray:
