@@ -10,14 +10,15 @@
 //     token blocks padded to 16.  A lane loads 8 consecutive columns of 4 rows (16 lanes x 16 bytes
 //     = 256 contiguous bytes per row), and a byte permute regroups those registers into the K-runs
 //     the instruction wants; the weight never passes through LDS.  Measured on MI355X this kernel is
-//     the fastest for every B >= 2 (LLaMA3-8B layer: 160 us at B = 2 and 4, 173 us at B = 16; the
-//     fp32-FMA kernel needs 205 us at B = 4), because the kernel is HBM-bound and the FMA variant
-//     spends its issue slots on B x 8 multiply-adds and coefficient reads per 16 bytes loaded;
+//     the fastest for every B >= 2 (the fp32-FMA kernel needed 205 us per LLaMA3-8B layer at B = 4 where
+//     this one needed 160 us), because the kernel is HBM-bound and the FMA variant spends its issue slots
+//     on B x 8 multiply-adds and coefficient reads per 16 bytes loaded;
 //   * an fp32-FMA kernel (2 or 4 tokens per workgroup) remains for the one case the 16-bit B
 //     operand cannot express: a per-channel coefficient scale applied in fp32 (learned pre-norm
 //     scale in front of an explicit rotation).
-// Work split, cross-workgroup hand-off and epilogue follow the single-token kernel
-// (gemv_core.hpp), with one arrival per workgroup for all its tokens.
+// Work split (one strip per workgroup, equal runs of rows), cross-workgroup hand-off (16-byte coherent
+// stores and loads, arrival counter, the last arrival finishes) and epilogue follow the single-token
+// kernel (gemv_core.hpp), with one arrival per workgroup for all its tokens.
 #include "gemv_core.hpp"
 
 namespace larosa {
