@@ -130,14 +130,15 @@ int run_gemv(GemvArgs a, bool bf16, void* ws, size_t ws_bytes, hipStream_t st) {
 // two jobs' sizes in strip-rows (512-column pieces of weight rows).  Measured on 7B-, 8B- and 70B-shaped
 // layers: 256 + 192 is best while one workgroup's share stays small; an adapter at least as large as
 // the projection takes half of the 512 resident slots; a projection several times the adapter whose
-// workgroups would each stream more than 1 MiB takes three quarters of them.
+// workgroups would each stream more than 1 MiB takes seven eighths of them (70B gate|up: 130 us with
+// 384 + 128, 125 with 448 + 128, 124 with 448 + 64, 137 with 224 + 128).
 struct SideSplit { int main_g, side_g; };
 SideSplit side_split(int d_out, int K, int side_d) {
   SideSplit r{256, 192};
   const long main_T = static_cast<long>((d_out + 511) / 512) * K;
   const long side_T = static_cast<long>((side_d + 511) / 512) * side_d;
   if (side_T >= main_T && side_T / 192 > 512) r = {256, 256};
-  else if (main_T >= 4 * side_T && main_T / 256 > 1024) r = {384, 128};
+  else if (main_T >= 4 * side_T && main_T / 256 > 1024) r = {448, 64};
   if (tuning().side_main_g > 0) r.main_g = tuning().side_main_g;
   if (tuning().side_g > 0) r.side_g = tuning().side_g;
   return r;
