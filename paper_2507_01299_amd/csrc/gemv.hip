@@ -62,7 +62,14 @@ GemvPlan plan_gemv(int d_out, int K, int g_hint, int strip_cols, int max_ranks) 
   if (wps > K / tuning().min_rows) wps = K / tuning().min_rows;
   if (wps < 1) wps = 1;
   long per = (K + wps - 1) / wps;
-  if (max_ranks > 0 && per > max_ranks) per = max_ranks;   // the workgroup's rank list must fit its LDS arrays
+  if (max_ranks > 0 && per > max_ranks) {
+    // The workgroup's rank list must fit its LDS arrays, so a strip needs more workgroups than one per
+    // compute unit allows.  Between one and two per unit some units carry twice the load of others: go to
+    // (at most) two per unit instead (70B gate|up alone: 121 us with 336 workgroups).
+    long need = (K + max_ranks - 1) / max_ranks;
+    if (g_hint == 0 && tuning().g_target == 0 && 512 / p.nstrips > need) need = 512 / p.nstrips;
+    per = (K + need - 1) / need;
+  }
   p.chunk = static_cast<int>(per);
   p.wps = static_cast<int>((K + per - 1) / per);           // every workgroup of a strip has ranks
   p.G = p.nstrips * p.wps;
