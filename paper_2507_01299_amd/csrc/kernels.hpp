@@ -38,7 +38,8 @@ struct GemvPlan {
 
 struct Tuning {
   int g_target = 0;           // target workgroups per launch; 0 = automatic (256 or 512)
-  int min_rows = 8;           // minimum row-strips per workgroup
+  int min_rows = 112;         // minimum kept rows per workgroup (14 per wave: fewer, fatter workgroups beat a full chip
+                              // for the o projection: 2457 rows over 21 instead of 32 workgroups per strip, -0.5 us)
   int variant = 0;            // row-waves per workgroup: 0 -> 8, 1 -> 16, 2 -> 4
   int fused = 1;              // decoder layer: 1 = Top-K fused into the projections, 0 = separate kernels
   int side_main_g = 0;        // workgroups of a projection that shares its launch with a shortcut adapter; 0 = by size

@@ -67,7 +67,7 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.larosa_set_tuning(99, 1) == api.EINVAL
     assert lib.larosa_set_tuning(4, 8) == api.EINVAL          # a key that no longer exists
     # every documented key accepts its default and rejects a value out of range
-    for key, good, bad in ((0, 0, -1), (1, 8, 0), (2, 0, 3), (3, 1, 2), (5, 0, 4), (6, 0, 4),
+    for key, good, bad in ((0, 0, -1), (1, 112, 0), (2, 0, 3), (3, 1, 2), (5, 0, 4), (6, 0, 4),
                            (7, 32768, 100), (8, 16384, 4), (9, 1, 2), (10, 0, 3)):
         assert lib.larosa_set_tuning(key, bad) == api.EINVAL
         assert lib.larosa_set_tuning(key, good) == api.OK
