@@ -60,6 +60,19 @@ def test_tiny_layer_every_stage(api, fused_mode, dtype, adapter):
     assert np.array_equal(to_bits(out), to_bits(out2))
 
 
+@pytest.mark.parametrize("B", [1, 2])
+@pytest.mark.parametrize("Ks", [(256, 256, 256, 704), (1, 1, 1, 1), (255, 1, 256, 703)])
+def test_degenerate_kept_counts(api, fused_mode, B, Ks):
+    """Everything kept (K = width: the sparsifier is the identity), one value kept, and one short of everything: the
+    select's thresholds sit at the ends of the key range, and the handed-down histograms are read at their first and
+    last bins."""
+    print(f"degenerate kept counts B={B} K={Ks} fused={fused_mode}", flush=True)
+    shape = synth.LayerShape("tiny", 256, 256, 128, 704, 32, "bf16")
+    case = cases.build_block_layer(shape, 0.4, seed=77, n_cal=1024, Ks=Ks)
+    xb, out, tr, dl, ws = _run_layer(api, case, B, seed=3)
+    check_layer_trace(case.layer, xb, tr, out)
+
+
 @pytest.mark.parametrize("B", [17, 40, 70])
 def test_large_batches_span_several_token_groups(api, B):
     """The batched kernels handle 16 or 32 tokens per group: batches that fill one group partly,
