@@ -844,7 +844,10 @@ int larosa_sparse_gemv_w4(const void* Wq, const void* scales, const void* h, con
   w.Wq = static_cast<const uint32_t*>(Wq);
   w.scales = static_cast<const uint16_t*>(scales);
   w.ng = (d_out + 127) / 128;
-  const GemvPlan p = plan_gemv(d_out, K, 0, w4_strip_cols(d_out));
+  // the 2048-column geometry has a quarter of the strips: two workgroups per compute unit keep enough loads in
+  // flight (70B gate|up: 47.1 us with 252 workgroups, 39.1 with 504)
+  const int strip_cols = w4_strip_cols(d_out);
+  const GemvPlan p = plan_gemv(d_out, K, strip_cols > 512 && tuning().g_target == 0 ? 512 : 0, strip_cols);
   if (static_cast<size_t>(B) * p.nstrips > kCounterSlots) return LAROSA_EUNSUPPORTED;
   const size_t need = kCounterBytes + static_cast<size_t>(B) * p.partial_floats * sizeof(float);
   if (!ws || !aligned(ws, 256) || ws_bytes < need) return LAROSA_EWORKSPACE;
